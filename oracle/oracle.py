@@ -1,0 +1,161 @@
+"""ctypes front end of the CPU oracle (oracle/ckpt_oracle.c).
+
+TEST INFRASTRUCTURE ONLY: imported by tests/, by __graft_entry__.smoke() and by
+bench.py's cpu_baseline leg.  Nothing in the GPU package imports this module
+and this module imports nothing from the GPU package.
+
+solve_chain / solve_batch evaluate the recurrence of the paper's Theorem
+(Section "Activation Checkpoint Solver / Modeling"); reconstruct() walks the
+recorded choices into the operation sequence of Table 1.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+INF = 1 << 30
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "ckpt_oracle.c")
+_LIB = os.path.join(_HERE, "libckpt_oracle.so")
+_lib = None
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (-O2, OpenMP).  Returns the library path."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
+                               "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        lib = ctypes.CDLL(build())
+        p32 = ctypes.POINTER(ctypes.c_int32)
+        lib.oracle_solve_chain.restype = ctypes.c_int
+        lib.oracle_solve_chain.argtypes = [ctypes.c_int, ctypes.c_int] + [p32] * 7 + [
+            p32, ctypes.POINTER(ctypes.c_int16), ctypes.c_int]
+        for f in (lib.oracle_m_all, lib.oracle_m_null):
+            f.restype = ctypes.c_int64
+            f.argtypes = [ctypes.c_int] + [p32] * 5 + [ctypes.c_int, ctypes.c_int]
+        lib.oracle_max_threads.restype = ctypes.c_int
+        _lib = lib
+    return _lib
+
+
+def _p(a, ct=ctypes.c_int32):
+    return a.ctypes.data_as(ctypes.POINTER(ct))
+
+
+def _i32(a):
+    a = np.ascontiguousarray(a, dtype=np.int32)
+    return a
+
+
+def max_threads() -> int:
+    return _load().oracle_max_threads()
+
+
+def solve_chain(L, M, uf, ub, wa, wabar, wdelta=None, of=None, ob=None, nthreads=1):
+    """One chain -> (cost int32 [L, L, M+1], choice int16 [L, L, M+1]).
+
+    Index [s-1, t-1, m]; entries with s > t are cost 0 / choice -1 (never written).
+    """
+    uf, ub, wa, wabar = map(_i32, (uf, ub, wa, wabar))
+    wd = wa if wdelta is None else _i32(wdelta)
+    of = np.zeros(L, np.int32) if of is None else _i32(of)
+    ob = np.zeros(L, np.int32) if ob is None else _i32(ob)
+    assert uf.shape == (L,) and ub.shape == (L,) and wabar.shape == (L,)
+    assert wa.shape == (L + 1,) and wd.shape == (L + 1,) and of.shape == (L,) and ob.shape == (L,)
+    cost = np.zeros((L, L, M + 1), np.int32)
+    choice = np.full((L, L, M + 1), -1, np.int16)
+    rc = _load().oracle_solve_chain(L, M, _p(uf), _p(ub), _p(wa), _p(wabar), _p(wd), _p(of), _p(ob),
+                                    _p(cost), _p(choice, ctypes.c_int16), int(nthreads))
+    if rc != 0:
+        raise ValueError("oracle_solve_chain: bad argument")
+    return cost, choice
+
+
+def solve_batch(batch, nthreads=1):
+    """workloads.ChainBatch -> list of (cost, choice) per chain."""
+    return [solve_chain(batch.L, batch.M, *batch.chain(b), nthreads=nthreads) for b in range(batch.B)]
+
+
+def thresholds(L, wa, wabar, wdelta, of, ob, s, t):
+    """(m_all^{s,t}, m_null^{s,t}) of the Theorem's last display."""
+    wa, wabar, wdelta, of, ob = map(_i32, (wa, wabar, wdelta, of, ob))
+    lib = _load()
+    args = (L, _p(wa), _p(wabar), _p(wdelta), _p(of), _p(ob), s, t)
+    return int(lib.oracle_m_all(*args)), int(lib.oracle_m_null(*args))
+
+
+# Operation kinds of Table 1.
+F_ALL, F_CK, F_NULL, BWD = 0, 1, 2, 3
+
+
+def reconstruct(choice, wa, wabar, s, t, m):
+    """Operation list [(kind, stage), ...] that realises C_BP(s, t, m).
+
+    Follows the recorded choice k of each visited cell: k == s with s == t is
+    F_all^s, B^s; k == s is F_all^s, the schedule of (s+1, t, m - omega_abar^s),
+    B^s (C_all of the Theorem); k = s' > s is F_ck^s, F_null^{s+1..s'-1}, the
+    schedule of (s', t, m - omega_a^{s'-1}), the schedule of (s, s'-1, m) (C_ck).
+    Raises ValueError on an infeasible cell.
+    """
+    if m < 0:
+        raise ValueError("infeasible")
+    k = int(choice[s - 1, t - 1, m])
+    if k == 0:
+        raise ValueError("infeasible")
+    if s == t:
+        return [(F_ALL, s), (BWD, s)]
+    if k == s:
+        return ([(F_ALL, s)] + reconstruct(choice, wa, wabar, s + 1, t, m - int(wabar[s - 1]))
+                + [(BWD, s)])
+    ops = [(F_CK, s)] + [(F_NULL, j) for j in range(s + 1, k)]
+    ops += reconstruct(choice, wa, wabar, k, t, m - int(wa[k - 1]))
+    ops += reconstruct(choice, wa, wabar, s, k - 1, m)
+    return ops
+
+
+def min_feasible_memory(L, wa, wabar, wdelta=None, of=None, ob=None):
+    """need[s-1, t-1] = smallest m with C_BP(s, t, m) finite (int64 [L, L], s <= t).
+
+    Scalar form of the Theorem's feasibility: a leaf needs m_all^{s,s}; storing stage s
+    needs max(m_all^{s,t}, omega_abar^s + need(s+1, t)); a checkpoint split at s' needs
+    max(m_null^{s,t}, omega_a^{s'-1} + need(s', t), need(s, s'-1)).
+    """
+    wa = np.asarray(wa, np.int64)
+    wabar = np.asarray(wabar, np.int64)
+    wd = wa if wdelta is None else np.asarray(wdelta, np.int64)
+    of = np.zeros(L, np.int64) if of is None else np.asarray(of, np.int64)
+    ob = np.zeros(L, np.int64) if ob is None else np.asarray(ob, np.int64)
+    need = np.zeros((L + 2, L + 2), np.int64)  # 1-based
+    for s in range(1, L + 1):
+        need[s, s] = max(wd[s] + wabar[s - 1] + of[s - 1], wd[s] + wabar[s - 1] + ob[s - 1])
+    for d in range(1, L):
+        for s in range(1, L - d + 1):
+            t = s + d
+            m_all = max(wd[t] + wabar[s - 1] + of[s - 1], wd[s] + wabar[s - 1] + ob[s - 1])
+            sweep = wa[s] + of[s - 1]
+            if t > s + 1:
+                j = np.arange(s + 1, t)
+                sweep = max(sweep, int((wa[j - 1] + wa[j] + of[j - 1]).max()))
+            m_null = wd[t] + sweep
+            sp = np.arange(s + 1, t + 1)
+            split = np.maximum(wa[sp - 1] + need[sp, t], need[s, sp - 1]).min()
+            need[s, t] = min(max(m_all, wabar[s - 1] + need[s + 1, t]), max(m_null, split))
+    return need[1:L + 1, 1:L + 1]
+
+
+def infeasible_fraction(L, M, wa, wabar, wdelta=None, of=None, ob=None):
+    """Fraction of the (s <= t, m in 0..M) cells of one chain that are infeasible."""
+    need = min_feasible_memory(L, wa, wabar, wdelta, of, ob)
+    iu = np.triu_indices(L)
+    return float(np.minimum(need[iu], M + 1).sum()) / (len(iu[0]) * (M + 1))
