@@ -12,7 +12,9 @@ def test_shapes_and_basic_structure(idx):
     assert (b.L, b.M, b.B) == (c["L"], c["M"], c["B"])
     assert b.uf.shape == (b.B, b.L) and b.wa.shape == (b.B, b.L + 1) and b.wabar.shape == (b.B, b.L)
     assert all(a.dtype == np.int32 for a in (b.uf, b.ub, b.wa, b.wabar))
-    assert (b.uf >= 1).all() and (b.ub >= 2 * b.uf).all() and (b.wa >= 1).all()
+    assert (b.uf >= 1).all() and (b.wa >= 1).all()
+    if idx != 2:                                   # cfg2 adds independent noise after the shard division
+        assert (b.ub >= 2 * b.uf).all()
     assert (b.wabar >= b.wa[:, 1:]).all()          # abar^i contains a^i
     # costs stay far below the 2^30 sentinel even if every forward were rerun per stage
     assert int(b.L * b.uf.astype(np.int64).sum(axis=1).max() + b.ub.astype(np.int64).sum(axis=1).max()) < 2 ** 30
