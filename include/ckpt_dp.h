@@ -1,0 +1,152 @@
+/*
+ * ckpt_dp.h - C ABI of the batched activation-checkpoint dynamic program for AMD
+ * MI355X (gfx950).
+ *
+ * The library fills, for B independent chains of L stages, the table
+ *     C_BP(s, t, m),  1 <= s <= t <= L,  m = 0..M
+ * of the paper's Theorem (Section "Activation Checkpoint Solver / Modeling"): the
+ * optimal time of a persistent schedule that back-propagates through stages s..t
+ * with m memory slots, together with the candidate that attains it, and turns one
+ * chain's recorded candidates into the operation sequence of Table 1.  The planner
+ * of Section "Integrate Two Solvers" re-solves the chain for every candidate
+ * intra-op plan, hence the batch.
+ *
+ * Conventions
+ *   - Stages are numbered 1..L, activations and gradients 0..L, as in the paper.
+ *   - All values are int32.  Times are arbitrary ticks, sizes are memory slots.
+ *     u_f / u_b already include the communication times of Table 2, o_f / o_b the
+ *     communication overheads.
+ *   - Infinity is CKPT_INF = 2^30.  A cell holds min(CKPT_INF, exact value); an
+ *     infeasible operand makes a candidate infeasible; a negative memory argument
+ *     is infeasible.
+ *   - Candidates of cell (s, t): k = s is C_all (keep abar^s; the only candidate
+ *     when s == t), k = s' in s+1..t is C_ck(s, s', t, m) (checkpoint a^{s-1}, run
+ *     forward to a^{s'-1}).  The recorded candidate is the smallest k that attains
+ *     the minimum, 0 when the cell is infeasible.
+ *   - m counts everything resident while s..t is processed except the segment's
+ *     input a^{s-1}; delta^t is counted.  The whole chain under a device budget of
+ *     M_total slots is cell (1, L, M_total - omega_a^0).
+ *
+ * Table layout (device memory, owned by the caller)
+ *   cost : int32  [B][ckpt_table_rows(L)][ckpt_row_pitch(M)]
+ *   arg  : uint8  [B][ckpt_table_rows(L)][ckpt_row_pitch(M)]
+ *   Row ckpt_row_index(L, s, t) of a chain holds cell (s, t) for m = 0..M in
+ *   columns 0..M; columns M+1..pitch-1 are padding with unspecified contents.
+ *   Rows are ordered by s, then t:  index = (s-1)*L - (s-1)*(s-2)/2 + (t-s).
+ *
+ * Ownership and threading: the library keeps no global state besides the last HIP
+ * error code; every buffer belongs to the caller and must stay valid until the
+ * work enqueued on the stream has finished.  Calls on different streams with
+ * disjoint buffers are independent.
+ *
+ * Errors: every function that can fail returns CKPT_OK (0) or a negative code and
+ * never throws or aborts.  Argument errors are reported before anything is
+ * enqueued.
+ */
+#ifndef CKPT_DP_H
+#define CKPT_DP_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define CKPT_INF (1 << 30)
+#define CKPT_MAX_L 254 /* the recorded candidate is one byte; 0 means infeasible */
+
+enum {
+    CKPT_OK = 0,
+    CKPT_E_ARG = -1,        /* null pointer, L < 1, M < 0, B < 1, s/t/m out of range */
+    CKPT_E_LIMIT = -2,      /* L > CKPT_MAX_L, or a table larger than 2^31-1 rows*pitch per chain */
+    CKPT_E_INFEASIBLE = -3, /* ckpt_schedule: the requested cell is infeasible */
+    CKPT_E_SMALLBUF = -4,   /* ckpt_schedule: ops_cap too small (2L-1 .. L(L+1)/2+L operations) */
+    CKPT_E_HIP = -5,        /* a HIP call failed; see ckpt_last_hip_error() */
+    CKPT_E_INPUT = -6,      /* ckpt_check_inputs: some chain violates the value preconditions */
+    CKPT_E_CORRUPT = -7     /* ckpt_schedule: the arg table is not one this library wrote */
+};
+
+/*
+ * Chain descriptors: DEVICE pointers, chain-major, int32.  Stage k of chain b is
+ * element [b*L + (k-1)] of the [B][L] arrays; activation / gradient i is element
+ * [b*(L+1) + i] of the [B][L+1] arrays.
+ * Preconditions on values (checked on the device, see ckpt_check_inputs): all >= 0;
+ * sum of u_f of a chain < 2^30 and every u_b < 2^30; every size and overhead
+ * <= 2^28.  Costs that reach 2^30 saturate to CKPT_INF exactly as defined above.
+ */
+typedef struct ckpt_chains {
+    const int32_t* uf;     /* [B][L]   u_f^k + u_fcomm^k            (Tables 1, 2) */
+    const int32_t* ub;     /* [B][L]   u_b^k + u_bcomm^k                          */
+    const int32_t* wa;     /* [B][L+1] omega_a^0..L                               */
+    const int32_t* wabar;  /* [B][L]   omega_abar^1..L                            */
+    const int32_t* wdelta; /* [B][L+1] omega_delta^0..L, or NULL: same as wa      */
+    const int32_t* of;     /* [B][L]   o_f^k + o_fcomm^k, or NULL: zeros          */
+    const int32_t* ob;     /* [B][L]   o_b^k + o_bcomm^k, or NULL: zeros          */
+} ckpt_chains_t;
+
+/* One operation of Table 1. */
+enum { CKPT_OP_F_ALL = 0, CKPT_OP_F_CK = 1, CKPT_OP_F_NULL = 2, CKPT_OP_B = 3 };
+typedef struct ckpt_op {
+    uint8_t kind;  /* CKPT_OP_* */
+    uint8_t stage; /* 1..L */
+} ckpt_op_t;
+
+/* Elements per table row: M+1 rounded up to a multiple of 64.  0 if M < 0. */
+size_t ckpt_row_pitch(int M);
+/* Rows per chain: L(L+1)/2.  0 if L < 1. */
+size_t ckpt_table_rows(int L);
+/* Row of cell (s, t), 1 <= s <= t <= L; -1 otherwise. */
+long ckpt_row_index(int L, int s, int t);
+/* Elements of the whole cost (or arg) table: B * rows * pitch.  0 on bad arguments. */
+size_t ckpt_table_elems(int L, int M, int B);
+/* Bytes of device workspace ckpt_solve_batched needs.  0 on bad arguments. */
+size_t ckpt_workspace_bytes(int L, int M, int B);
+
+/*
+ * Fill cost and arg for all B chains (Theorem, all three displays: the recurrence,
+ * C_ck / C_all, and the thresholds m_null / m_all).
+ *   chains    host pointer to a struct of DEVICE pointers (read during the call
+ *             only; the arrays it names are read by the enqueued kernels)
+ *   stream    a hipStream_t (NULL = the default stream); the call only enqueues
+ *             work and returns, it does not synchronise and allocates nothing
+ *   cost, arg DEVICE tables laid out as above, 256-byte aligned
+ *   workspace DEVICE memory of ckpt_workspace_bytes(L, M, B) bytes, 256-byte
+ *             aligned; holds per-chain prefix sums, thresholds and input flags
+ * Returns CKPT_OK, CKPT_E_ARG, CKPT_E_LIMIT or CKPT_E_HIP.
+ */
+int ckpt_solve_batched(const ckpt_chains_t* chains, int L, int M, int B, void* stream,
+                       int32_t* cost, uint8_t* arg, void* workspace);
+
+/*
+ * After ckpt_solve_batched on the same stream: wait for the stream and copy the
+ * per-chain input flags (0 = chain met the value preconditions) into flags_host[B]
+ * (HOST memory).  Returns CKPT_OK, CKPT_E_INPUT if any flag is nonzero (the
+ * tables of such a chain are unspecified, all memory accesses stayed in bounds),
+ * CKPT_E_ARG or CKPT_E_HIP.  Bits: 1 negative value, 2 time too large, 4 size too large.
+ */
+int ckpt_check_inputs(const void* workspace, int L, int M, int B, void* stream, int32_t* flags_host);
+
+/*
+ * Rebuild the operation sequence that realises C_BP(s, t, m_budget) of ONE chain
+ * from its recorded candidates (C_ck / C_all of the Theorem read backwards; the
+ * operations are those of Table 1, and consecutive F_null runs are what the
+ * code generator of Section "Code generation" wraps in a checkpoint block).
+ *   arg_host  HOST copy of that chain's arg table [rows][pitch]
+ *   wa, wabar HOST arrays of that chain: omega_a^0..L [L+1], omega_abar^1..L [L]
+ *   ops_out   HOST array of ops_cap operations, written in execution order
+ * Returns the number of operations (>= 2), or CKPT_E_ARG, CKPT_E_LIMIT,
+ * CKPT_E_INFEASIBLE, CKPT_E_SMALLBUF, CKPT_E_CORRUPT.  Runs on the host only.
+ */
+int ckpt_schedule(const uint8_t* arg_host, const int32_t* wa, const int32_t* wabar, int L, int M,
+                  int s, int t, int m_budget, ckpt_op_t* ops_out, int ops_cap);
+
+/* hipError_t of the most recent failed HIP call made by this library (0 if none). */
+int ckpt_last_hip_error(void);
+/* Static description of a CKPT_* code. */
+const char* ckpt_strerror(int code);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* CKPT_DP_H */

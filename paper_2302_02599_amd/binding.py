@@ -1,0 +1,183 @@
+"""ctypes binding of include/ckpt_dp.h.  Argument marshalling only.
+
+PyTorch supplies device memory and the stream; no arithmetic of the method
+happens in this file.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+from typing import Optional
+
+import numpy as np
+
+CKPT_INF = 1 << 30
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libckpt_dp.so")
+_lib = None
+
+
+class CkptError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        msg = load_library().ckpt_strerror(code).decode()
+        extra = f" (hipError {load_library().ckpt_last_hip_error()})" if code == -5 else ""
+        super().__init__(f"{where}: {msg}{extra} [{code}]")
+
+
+class _Chains(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_void_p) for n in ("uf", "ub", "wa", "wabar", "wdelta", "of", "ob")]
+
+
+class _Op(ctypes.Structure):
+    _fields_ = [("kind", ctypes.c_uint8), ("stage", ctypes.c_uint8)]
+
+
+def lib_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the in-tree HIP library.  Raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is missing: run `python paper_2302_02599_amd/build.py` "
+                          "(or __graft_entry__.build()) first; there is no fallback path")
+    lib = ctypes.CDLL(_LIB_PATH)
+    sz, i, vp = ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p
+    lib.ckpt_row_pitch.restype, lib.ckpt_row_pitch.argtypes = sz, [i]
+    lib.ckpt_table_rows.restype, lib.ckpt_table_rows.argtypes = sz, [i]
+    lib.ckpt_row_index.restype, lib.ckpt_row_index.argtypes = ctypes.c_long, [i, i, i]
+    lib.ckpt_table_elems.restype, lib.ckpt_table_elems.argtypes = sz, [i, i, i]
+    lib.ckpt_workspace_bytes.restype, lib.ckpt_workspace_bytes.argtypes = sz, [i, i, i]
+    lib.ckpt_solve_batched.restype = i
+    lib.ckpt_solve_batched.argtypes = [ctypes.POINTER(_Chains), i, i, i, vp, vp, vp, vp]
+    lib.ckpt_check_inputs.restype = i
+    lib.ckpt_check_inputs.argtypes = [vp, i, i, i, vp, vp]
+    lib.ckpt_schedule.restype = i
+    lib.ckpt_schedule.argtypes = [vp, vp, vp, i, i, i, i, i, ctypes.POINTER(_Op), i]
+    lib.ckpt_last_hip_error.restype, lib.ckpt_last_hip_error.argtypes = i, []
+    lib.ckpt_strerror.restype, lib.ckpt_strerror.argtypes = ctypes.c_char_p, [i]
+    _lib = lib
+    return lib
+
+
+def ckpt_row_pitch(M: int) -> int:
+    return load_library().ckpt_row_pitch(M)
+
+
+def ckpt_table_rows(L: int) -> int:
+    return load_library().ckpt_table_rows(L)
+
+
+def ckpt_row_index(L: int, s: int, t: int) -> int:
+    return load_library().ckpt_row_index(L, s, t)
+
+
+def ckpt_table_elems(L: int, M: int, B: int) -> int:
+    return load_library().ckpt_table_elems(L, M, B)
+
+
+def ckpt_workspace_bytes(L: int, M: int, B: int) -> int:
+    return load_library().ckpt_workspace_bytes(L, M, B)
+
+
+def _dev_ptr(t, name, shape):
+    import torch
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == torch.int32 and t.is_contiguous()):
+        raise TypeError(f"{name}: expected a contiguous int32 device tensor")
+    if tuple(t.shape) != shape:
+        raise ValueError(f"{name}: shape {tuple(t.shape)} != {shape}")
+    return t.data_ptr()
+
+
+def ckpt_solve_batched(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, *, wdelta=None, of=None, ob=None,
+                       stream=None) -> None:
+    """Enqueue the table fill on ``stream`` (default: torch's current stream).
+
+    uf, ub, wabar, of, ob: int32 device tensors [B, L]; wa, wdelta: [B, L+1];
+    cost: int32 device tensor of ckpt_table_elems elements; arg: uint8, same count;
+    workspace: uint8 device tensor of at least ckpt_workspace_bytes bytes.
+    """
+    import torch
+    ch = _Chains(_dev_ptr(uf, "uf", (B, L)), _dev_ptr(ub, "ub", (B, L)), _dev_ptr(wa, "wa", (B, L + 1)),
+                 _dev_ptr(wabar, "wabar", (B, L)), _dev_ptr(wdelta, "wdelta", (B, L + 1)),
+                 _dev_ptr(of, "of", (B, L)), _dev_ptr(ob, "ob", (B, L)))
+    n = ckpt_table_elems(L, M, B)
+    if n and (cost.numel() < n or arg.numel() < n or cost.dtype != torch.int32 or arg.dtype != torch.uint8):
+        raise ValueError("cost/arg tables too small or of the wrong dtype")
+    if n and workspace.numel() * workspace.element_size() < ckpt_workspace_bytes(L, M, B):
+        raise ValueError("workspace too small")
+    st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    rc = load_library().ckpt_solve_batched(ctypes.byref(ch), L, M, B, ctypes.c_void_p(st), cost.data_ptr(),
+                                           arg.data_ptr(), workspace.data_ptr())
+    if rc != 0:
+        raise CkptError(rc, "ckpt_solve_batched")
+
+
+def ckpt_check_inputs(workspace, L, M, B, *, stream=None) -> np.ndarray:
+    """Synchronise and return the per-chain input flags (all zero = fine); raises on nonzero."""
+    import torch
+    flags = np.zeros(B, np.int32)
+    st = torch.cuda.current_stream().cuda_stream if stream is None else stream
+    rc = load_library().ckpt_check_inputs(workspace.data_ptr(), L, M, B, ctypes.c_void_p(st),
+                                          flags.ctypes.data)
+    if rc not in (0, -6):
+        raise CkptError(rc, "ckpt_check_inputs")
+    return flags
+
+
+def ckpt_schedule(arg_host: np.ndarray, wa: np.ndarray, wabar: np.ndarray, L: int, M: int, s: int, t: int,
+                  m_budget: int, ops_cap: Optional[int] = None):
+    """Operation list [(kind, stage), ...] of cell (s, t, m_budget) of one chain (host only)."""
+    arg_host = np.ascontiguousarray(arg_host, dtype=np.uint8)
+    wa = np.ascontiguousarray(wa, dtype=np.int32)
+    wabar = np.ascontiguousarray(wabar, dtype=np.int32)
+    if arg_host.size < ckpt_table_rows(L) * ckpt_row_pitch(M) or wa.size < L + 1 or wabar.size < L:
+        raise ValueError("ckpt_schedule: array too small")
+    cap = L * (L + 1) // 2 + L if ops_cap is None else ops_cap
+    ops = (_Op * max(cap, 1))()
+    rc = load_library().ckpt_schedule(arg_host.ctypes.data, wa.ctypes.data, wabar.ctypes.data, L, M, s, t,
+                                      m_budget, ops, cap)
+    if rc < 0:
+        raise CkptError(rc, "ckpt_schedule")
+    return [(ops[i].kind, ops[i].stage) for i in range(rc)]
+
+
+@dataclass
+class Solution:
+    """Device tables of one solve, with the logical [B, rows, pitch] views."""
+    L: int
+    M: int
+    B: int
+    cost: "object"      # int32 [B, rows, pitch] device tensor
+    arg: "object"       # uint8 [B, rows, pitch] device tensor
+    workspace: "object"
+
+
+def solve(batch, device="cuda:0", check=True) -> Solution:
+    """Convenience wrapper: upload a workloads.ChainBatch-like object, allocate tables, solve."""
+    import torch
+    dev = torch.device(device)
+    L, M, B = batch.L, batch.M, batch.B
+
+    def up(a):
+        return None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).to(dev)
+
+    rows, pitch = ckpt_table_rows(L), ckpt_row_pitch(M)
+    with torch.cuda.device(dev):
+        cost = torch.empty((B, rows, pitch), dtype=torch.int32, device=dev)
+        arg = torch.empty((B, rows, pitch), dtype=torch.uint8, device=dev)
+        ws = torch.empty(ckpt_workspace_bytes(L, M, B), dtype=torch.uint8, device=dev)
+        ckpt_solve_batched(up(batch.uf), up(batch.ub), up(batch.wa), up(batch.wabar), L, M, B, cost, arg, ws,
+                           wdelta=up(batch.wdelta), of=up(batch.of), ob=up(batch.ob))
+        if check:
+            flags = ckpt_check_inputs(ws, L, M, B)
+            if flags.any():
+                raise CkptError(-6, f"solve (flags {flags.tolist()})")
+    return Solution(L, M, B, cost, arg, ws)

@@ -1,0 +1,134 @@
+"""Host-side checks of the C ABI: exported symbols, layout helpers, error codes and
+ckpt_schedule (which runs on the host).  No GPU compute is called here."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from persistent_bruteforce import simulate
+from workloads import make_config, random_chain_batch
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def amd():
+    import paper_2302_02599_amd as amd
+    if not os.path.exists(amd.lib_path()):
+        from paper_2302_02599_amd.build import build_library
+        build_library()
+    amd.load_library()
+    return amd
+
+
+def test_library_exports_every_declared_symbol(amd):
+    header = open(os.path.join(ROOT, "include", "ckpt_dp.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = set(re.findall(r"\b(ckpt_[a-z_]+)\s*\(", header))
+    assert {"ckpt_solve_batched", "ckpt_schedule", "ckpt_workspace_bytes", "ckpt_row_index"} <= names
+    lib = ctypes.CDLL(amd.lib_path())
+    for n in sorted(names):
+        assert hasattr(lib, n), n
+
+
+def test_layout_helpers(amd):
+    assert amd.ckpt_row_pitch(0) == 64 and amd.ckpt_row_pitch(63) == 64 and amd.ckpt_row_pitch(64) == 128
+    assert amd.ckpt_row_pitch(4096) == 4160 and amd.ckpt_row_pitch(-1) == 0
+    for L in (1, 2, 7, 24):
+        seen = []
+        for s in range(1, L + 1):
+            for t in range(s, L + 1):
+                seen.append(amd.ckpt_row_index(L, s, t))
+        assert seen == list(range(L * (L + 1) // 2))      # ordered by s then t, no gaps
+        assert amd.ckpt_table_rows(L) == len(seen)
+    assert amd.ckpt_row_index(5, 3, 2) == -1 and amd.ckpt_row_index(5, 0, 2) == -1 and amd.ckpt_row_index(5, 1, 6) == -1
+    assert amd.ckpt_table_elems(8, 64, 2) == 2 * 36 * 128
+    assert amd.ckpt_workspace_bytes(0, 4, 1) == 0 and amd.ckpt_workspace_bytes(8, 64, 1) > 0
+
+
+def test_solve_rejects_bad_arguments_before_touching_the_gpu(amd):
+    lib = amd.load_library()
+    from paper_2302_02599_amd.binding import _Chains
+    ch = _Chains(256, 256, 256, 256, None, None, None)
+    f = lib.ckpt_solve_batched
+    assert f(None, 4, 8, 1, None, 256, 256, 256) == -1
+    assert f(ctypes.byref(ch), 0, 8, 1, None, 256, 256, 256) == -1
+    assert f(ctypes.byref(ch), 4, -1, 1, None, 256, 256, 256) == -1
+    assert f(ctypes.byref(ch), 4, 8, 0, None, 256, 256, 256) == -1
+    assert f(ctypes.byref(ch), 255, 8, 1, None, 256, 256, 256) == -2          # arg is one byte
+    assert f(ctypes.byref(ch), 254, 2 ** 20, 1, None, 256, 256, 256) == -2    # table beyond int32 indexing
+    assert f(ctypes.byref(ch), 4, 8, 1, None, 260, 256, 256) == -1            # misaligned table
+    assert f(ctypes.byref(ch), 4, 8, 1, None, None, 256, 256) == -1
+    ch2 = _Chains(256, None, 256, 256, None, None, None)
+    assert f(ctypes.byref(ch2), 4, 8, 1, None, 256, 256, 256) == -1
+    assert lib.ckpt_strerror(-2) == b"size limit exceeded"
+
+
+def _arg_table_from_oracle(amd, choice, L, M):
+    pitch = amd.ckpt_row_pitch(M)
+    tab = np.full((amd.ckpt_table_rows(L), pitch), 0xEE, np.uint8)   # padding holds junk
+    for s in range(1, L + 1):
+        for t in range(s, L + 1):
+            tab[amd.ckpt_row_index(L, s, t), :M + 1] = choice[s - 1, t - 1]
+    return tab
+
+
+@pytest.mark.parametrize("which", ["cfg0", "cfg1", "rand"])
+def test_schedule_matches_oracle_and_simulator(amd, oracle_mod, which):
+    batch = {"cfg0": lambda: make_config(0), "cfg1": lambda: make_config(1),
+             "rand": lambda: random_chain_batch(11, 70, 1, 31, overheads=True, own_wdelta=True)}[which]()
+    L, M = batch.L, batch.M
+    ch = batch.chain(0)
+    cost, choice = oracle_mod.solve_chain(L, M, *ch)
+    tab = _arg_table_from_oracle(amd, choice, L, M)
+    n_checked = 0
+    for (s, t) in [(1, L), (2, L), (1, L - 1), (L // 2, L // 2)]:
+        for m in range(0, M + 1, max(1, M // 25)):
+            if cost[s - 1, t - 1, m] >= oracle_mod.INF:
+                with pytest.raises(amd.CkptError) as e:
+                    amd.ckpt_schedule(tab, ch[2], ch[3], L, M, s, t, m)
+                assert e.value.code == -3
+                continue
+            ops = amd.ckpt_schedule(tab, ch[2], ch[3], L, M, s, t, m)
+            assert ops == oracle_mod.reconstruct(choice, ch[2], ch[3], s, t, m)
+            time, peak = simulate(ops, s, t, *ch)
+            assert time == cost[s - 1, t - 1, m] and peak <= m
+            n_checked += 1
+    assert n_checked > 10
+
+
+def test_schedule_error_codes(amd, oracle_mod):
+    batch = make_config(0)
+    L, M = batch.L, batch.M
+    ch = batch.chain(0)
+    _, choice = oracle_mod.solve_chain(L, M, *ch)
+    tab = _arg_table_from_oracle(amd, choice, L, M)
+    full = amd.ckpt_schedule(tab, ch[2], ch[3], L, M, 1, L, M)
+    for bad in [dict(s=0), dict(t=L + 1), dict(s=3, t=2), dict(m_budget=-1), dict(m_budget=M + 1)]:
+        kw = dict(s=1, t=L, m_budget=M); kw.update(bad)
+        with pytest.raises(amd.CkptError) as e:
+            amd.ckpt_schedule(tab, ch[2], ch[3], L, M, kw["s"], kw["t"], kw["m_budget"])
+        assert e.value.code == -1
+    with pytest.raises(amd.CkptError) as e:
+        amd.ckpt_schedule(tab, ch[2], ch[3], L, M, 1, L, M, ops_cap=len(full) - 1)
+    assert e.value.code == -4
+    assert amd.ckpt_schedule(tab, ch[2], ch[3], L, M, 1, L, M, ops_cap=len(full)) == full
+    broken = tab.copy()
+    broken[amd.ckpt_row_index(L, 1, L), M] = L + 3          # candidate outside [s, t]
+    with pytest.raises(amd.CkptError) as e:
+        amd.ckpt_schedule(broken, ch[2], ch[3], L, M, 1, L, M)
+    assert e.value.code == -7
+
+
+def test_schedule_worst_case_length_fits_default_capacity(amd):
+    # a table that always splits at s' = t gives the longest sequence: L(L+1)/2 + L operations
+    L, M = 9, 3
+    pitch = amd.ckpt_row_pitch(M)
+    tab = np.zeros((amd.ckpt_table_rows(L), pitch), np.uint8)
+    for s in range(1, L + 1):
+        for t in range(s, L + 1):
+            tab[amd.ckpt_row_index(L, s, t), :] = t
+    ops = amd.ckpt_schedule(tab, np.zeros(L + 1, np.int32), np.zeros(L, np.int32), L, M, 1, L, M)
+    assert len(ops) == L * (L + 1) // 2 + L

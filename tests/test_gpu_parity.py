@@ -1,0 +1,171 @@
+"""GPU parity: the HIP tables equal the CPU oracle's bit for bit (cost and recorded candidate).
+
+All calls go through the C ABI (paper_2302_02599_amd.binding).  Integer work: the bar is
+exact equality of every cell."""
+import numpy as np
+import pytest
+
+from gpu_util import assert_tables_equal
+from persistent_bruteforce import simulate
+from workloads import ChainBatch, make_config, random_chain_batch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def amd():
+    import torch
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    import paper_2302_02599_amd as amd
+    amd.load_library()          # raises if the HIP library is not built: there is no fallback
+    return amd
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2])
+def test_configs_small(amd, oracle_mod, cfg):
+    batch = make_config(cfg)
+    print(f"case {batch.name}", flush=True)
+    assert_tables_equal(oracle_mod, batch, amd.solve(batch), nthreads=8)
+
+
+@pytest.mark.parametrize("L,M,B,seed,ovh,wd,zero", [
+    (1, 0, 1, 1, False, False, False), (1, 40, 3, 2, True, True, False),
+    (2, 63, 2, 3, True, False, False), (3, 64, 2, 4, False, True, False),
+    (7, 65, 3, 5, True, True, False), (8, 127, 2, 6, False, False, True),
+    (9, 200, 2, 7, True, True, False), (13, 129, 2, 8, True, False, False),
+    (16, 255, 2, 9, False, False, False), (17, 256, 3, 10, True, True, True),
+    (23, 300, 2, 11, True, True, False), (31, 513, 2, 12, False, True, False),
+    (33, 97, 5, 13, True, False, False), (40, 1, 2, 14, False, False, False),
+])
+def test_ragged_shapes(amd, oracle_mod, L, M, B, seed, ovh, wd, zero):
+    """Chain lengths and budgets that are not multiples of any tile, incl. M = 0 and L = 1."""
+    batch = random_chain_batch(L, M, B, seed, size_hi=max(2, min(9, (M + 8) // 8)), overheads=ovh,
+                               own_wdelta=wd, zero_sizes=zero)
+    print(f"case {batch.name}", flush=True)
+    assert_tables_equal(oracle_mod, batch, amd.solve(batch), nthreads=4)
+
+
+def test_everything_infeasible(amd, oracle_mod):
+    batch = random_chain_batch(12, 3, 2, 21, size_hi=9)
+    batch.wa += 5
+    batch.wabar += 5
+    sol = amd.solve(batch)
+    assert_tables_equal(oracle_mod, batch, sol)
+    assert (sol.cost[:, :, :batch.M + 1] == amd.CKPT_INF).all() and (sol.arg[:, :, :batch.M + 1] == 0).all()
+
+
+def test_costs_saturate_at_the_sentinel(amd, oracle_mod):
+    """Times large enough that long segments pass 2^30: those cells hold exactly the sentinel."""
+    batch = random_chain_batch(6, 80, 2, 22, size_hi=5)
+    batch.uf[:] = 150_000_000 + np.arange(6, dtype=np.int32)
+    batch.ub[:] = 300_000_000 - np.arange(6, dtype=np.int32)
+    sol = amd.solve(batch)
+    assert_tables_equal(oracle_mod, batch, sol)
+    root = sol.cost[0, amd.ckpt_row_index(6, 1, 6), batch.M].item()
+    one = sol.cost[0, amd.ckpt_row_index(6, 2, 2), batch.M].item()
+    assert root == amd.CKPT_INF and one == 450_000_000
+
+
+def test_abar_smaller_than_a_follows_the_printed_formulas(amd, oracle_mod):
+    rng = np.random.default_rng(23)
+    L, M, B = 14, 90, 2
+    batch = ChainBatch("abar_lt_a", L, M, B,
+                       uf=rng.integers(1, 50, (B, L)).astype(np.int32), ub=rng.integers(1, 90, (B, L)).astype(np.int32),
+                       wa=rng.integers(1, 9, (B, L + 1)).astype(np.int32), wabar=rng.integers(0, 6, (B, L)).astype(np.int32),
+                       wdelta=rng.integers(0, 7, (B, L + 1)).astype(np.int32),
+                       of=rng.integers(0, 4, (B, L)).astype(np.int32), ob=rng.integers(0, 4, (B, L)).astype(np.int32))
+    assert_tables_equal(oracle_mod, batch, amd.solve(batch))
+
+
+def test_sizes_larger_than_the_budget(amd, oracle_mod):
+    """A stage whose activation exceeds M + 1: shifts beyond the row stay in bounds and read as infeasible."""
+    batch = random_chain_batch(10, 50, 2, 24, size_hi=6)
+    batch.wa[:, 4] = 5000
+    batch.wabar[:, 6] = 70
+    assert_tables_equal(oracle_mod, batch, amd.solve(batch))
+
+
+def test_bad_inputs_are_flagged_not_faulted(amd):
+    import torch
+    batch = random_chain_batch(9, 60, 3, 25)
+    batch.uf[1, 3] = -7
+    batch.wa[2, 2] = -3
+    batch.wabar[2, 5] = (1 << 28) + 1
+    sol = amd.solve(batch, check=False)
+    flags = amd.ckpt_check_inputs(sol.workspace, batch.L, batch.M, batch.B)
+    torch.cuda.synchronize()
+    assert flags[0] == 0 and flags[1] & 1 and flags[2] & 1 and flags[2] & 4
+    with pytest.raises(amd.CkptError):
+        amd.solve(batch)
+
+
+def test_two_solves_are_bit_identical(amd):
+    batch = make_config(2)
+    a, b = amd.solve(batch), amd.solve(batch)
+    M = batch.M
+    assert (a.cost[:, :, :M + 1] == b.cost[:, :, :M + 1]).all() and (a.arg[:, :, :M + 1] == b.arg[:, :, :M + 1]).all()
+
+
+def test_schedule_from_gpu_table_runs_in_budget(amd, oracle_mod):
+    batch = make_config(1)
+    L, M = batch.L, batch.M
+    ch = batch.chain(0)
+    sol = amd.solve(batch)
+    arg_h = sol.arg[0].cpu().numpy()
+    cost_h = sol.cost[0].cpu().numpy()
+    root = amd.ckpt_row_index(L, 1, L)
+    checked = 0
+    for m in range(0, M + 1, 16):
+        if cost_h[root, m] >= amd.CKPT_INF:
+            continue
+        ops = amd.ckpt_schedule(arg_h, ch[2], ch[3], L, M, 1, L, m)
+        time, peak = simulate(ops, 1, L, *ch)
+        assert time == cost_h[root, m] and peak <= m
+        checked += 1
+    assert checked > 5
+
+
+def test_solve_on_a_side_stream(amd, oracle_mod):
+    import torch
+    batch = make_config(1)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        sol = amd.solve(batch)
+    st.synchronize()
+    assert_tables_equal(oracle_mod, batch, sol)
+
+
+_full = {}
+
+
+def _full_solution(amd, cfg):
+    """Solve a large configuration once per test session (the launch configuration the benchmark times)."""
+    import torch
+    if cfg not in _full:
+        _full.clear()                       # keep one multi-GB table set alive at a time
+        torch.cuda.empty_cache()
+        batch = make_config(cfg)
+        sol = amd.solve(batch)
+        torch.cuda.synchronize()
+        _full[cfg] = (batch, sol)
+    return _full[cfg]
+
+
+@pytest.mark.parametrize("cfg,group", [(3, g) for g in range(8)] + [(4, g) for g in range(8)])
+def test_configs_full_size(amd, oracle_mod, cfg, group):
+    """The two large configurations: full tables of every chain (cfg 3: eight chains per case,
+    cfg 4: one chain per case).  The oracle runs on all host cores."""
+    batch, sol = _full_solution(amd, cfg)
+    per = batch.B // 8
+    chains = list(range(group * per, (group + 1) * per))
+    print(f"case {batch.name} chains {chains}", flush=True)
+    nthreads = min(16, oracle_mod.max_threads())
+    assert_tables_equal(oracle_mod, batch, sol, nthreads=nthreads, chains=chains)
+
+
+def test_cfg4_infeasible_share(amd):
+    batch, sol = _full_solution(amd, 4)
+    n_inf = sum(int((sol.cost[b, :, :batch.M + 1] == amd.CKPT_INF).sum()) for b in range(batch.B))
+    frac = n_inf / (batch.B * amd.ckpt_table_rows(batch.L) * (batch.M + 1))
+    assert abs(frac - 0.30) < 0.01, frac
+    _full.clear()
