@@ -119,6 +119,21 @@ int ckpt_solve_batched(const ckpt_chains_t* chains, int L, int M, int B, void* s
                        int32_t* cost, uint8_t* arg, void* workspace);
 
 /*
+ * Measurement aid: the same fill as ckpt_solve_batched, with a HIP event recorded on
+ * the stream after every kernel launch.  The call waits for the stream, then adds the
+ * elapsed time between consecutive events to the kernel kind launched in between
+ * (so a kind's time includes the idle gap before each of its launches).
+ *   kind_ms, kind_launches   HOST arrays of CKPT_N_KERNEL_KINDS entries, overwritten
+ * Creates and destroys events (allocates); not for latency-critical callers.
+ * Returns as ckpt_solve_batched.
+ */
+enum { CKPT_K_PRECOMPUTE = 0, CKPT_K_DIAG = 1, CKPT_N_KERNEL_KINDS = 2 };
+int ckpt_solve_profiled(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
+                        uint8_t* arg, void* workspace, float* kind_ms, int* kind_launches);
+/* Name of a kernel kind as it appears in a rocprofv3 kernel trace; NULL if out of range. */
+const char* ckpt_kernel_name(int kind);
+
+/*
  * After ckpt_solve_batched on the same stream: wait for the stream and copy the
  * per-chain input flags (0 = chain met the value preconditions) into flags_host[B]
  * (HOST memory).  Returns CKPT_OK, CKPT_E_INPUT if any flag is nonzero (the

@@ -55,6 +55,9 @@ def load_library():
     lib.ckpt_workspace_bytes.restype, lib.ckpt_workspace_bytes.argtypes = sz, [i, i, i]
     lib.ckpt_solve_batched.restype = i
     lib.ckpt_solve_batched.argtypes = [ctypes.POINTER(_Chains), i, i, i, vp, vp, vp, vp]
+    lib.ckpt_solve_profiled.restype = i
+    lib.ckpt_solve_profiled.argtypes = [ctypes.POINTER(_Chains), i, i, i, vp, vp, vp, vp, vp, vp]
+    lib.ckpt_kernel_name.restype, lib.ckpt_kernel_name.argtypes = ctypes.c_char_p, [i]
     lib.ckpt_check_inputs.restype = i
     lib.ckpt_check_inputs.argtypes = [vp, i, i, i, vp, vp]
     lib.ckpt_schedule.restype = i
@@ -96,14 +99,7 @@ def _dev_ptr(t, name, shape):
     return t.data_ptr()
 
 
-def ckpt_solve_batched(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, *, wdelta=None, of=None, ob=None,
-                       stream=None) -> None:
-    """Enqueue the table fill on ``stream`` (default: torch's current stream).
-
-    uf, ub, wabar, of, ob: int32 device tensors [B, L]; wa, wdelta: [B, L+1];
-    cost: int32 device tensor of ckpt_table_elems elements; arg: uint8, same count;
-    workspace: uint8 device tensor of at least ckpt_workspace_bytes bytes.
-    """
+def _marshal(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, wdelta, of, ob, stream):
     import torch
     ch = _Chains(_dev_ptr(uf, "uf", (B, L)), _dev_ptr(ub, "ub", (B, L)), _dev_ptr(wa, "wa", (B, L + 1)),
                  _dev_ptr(wabar, "wabar", (B, L)), _dev_ptr(wdelta, "wdelta", (B, L + 1)),
@@ -114,8 +110,37 @@ def ckpt_solve_batched(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, *, wdel
     if n and workspace.numel() * workspace.element_size() < ckpt_workspace_bytes(L, M, B):
         raise ValueError("workspace too small")
     st = torch.cuda.current_stream().cuda_stream if stream is None else stream
-    rc = load_library().ckpt_solve_batched(ctypes.byref(ch), L, M, B, ctypes.c_void_p(st), cost.data_ptr(),
-                                           arg.data_ptr(), workspace.data_ptr())
+    return ch, ctypes.c_void_p(st)
+
+
+def ckpt_solve_profiled(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, *, wdelta=None, of=None, ob=None,
+                        stream=None):
+    """Same fill with per-kernel-kind timing; returns {kernel name: (total ms, launches)}. Synchronises."""
+    lib = load_library()
+    ch, st = _marshal(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, wdelta, of, ob, stream)
+    n = 0
+    while lib.ckpt_kernel_name(n) is not None:
+        n += 1
+    ms = (ctypes.c_float * n)()
+    cnt = (ctypes.c_int * n)()
+    rc = lib.ckpt_solve_profiled(ctypes.byref(ch), L, M, B, st, cost.data_ptr(), arg.data_ptr(),
+                                 workspace.data_ptr(), ms, cnt)
+    if rc != 0:
+        raise CkptError(rc, "ckpt_solve_profiled")
+    return {lib.ckpt_kernel_name(k).decode(): (float(ms[k]), int(cnt[k])) for k in range(n)}
+
+
+def ckpt_solve_batched(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, *, wdelta=None, of=None, ob=None,
+                       stream=None) -> None:
+    """Enqueue the table fill on ``stream`` (default: torch's current stream).
+
+    uf, ub, wabar, of, ob: int32 device tensors [B, L]; wa, wdelta: [B, L+1];
+    cost: int32 device tensor of ckpt_table_elems elements; arg: uint8, same count;
+    workspace: uint8 device tensor of at least ckpt_workspace_bytes bytes.
+    """
+    ch, st = _marshal(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, wdelta, of, ob, stream)
+    rc = load_library().ckpt_solve_batched(ctypes.byref(ch), L, M, B, st, cost.data_ptr(), arg.data_ptr(),
+                                           workspace.data_ptr())
     if rc != 0:
         raise CkptError(rc, "ckpt_solve_batched")
 

@@ -8,6 +8,7 @@
 #include <atomic>
 #include <cstdint>
 #include <cstring>
+#include <vector>
 
 #include "ckpt_dp.h"
 
@@ -171,6 +172,50 @@ int check_dims(int L, int M, int B) {
     return CKPT_OK;
 }
 
+// Optional per-launch event trail of ckpt_solve_profiled.
+struct Profile {
+    hipStream_t stream = nullptr;
+    std::vector<hipEvent_t> events;
+    std::vector<int> kinds;
+    bool mark(int kind) {
+        hipEvent_t e;
+        if (!hip_ok(hipEventCreate(&e))) return false;
+        events.push_back(e);
+        kinds.push_back(kind);
+        return hip_ok(hipEventRecord(e, stream));
+    }
+};
+
+#define CKPT_AFTER_LAUNCH(kind)                                   \
+    do {                                                          \
+        if (!hip_ok(hipGetLastError())) return CKPT_E_HIP;        \
+        if (prof && !prof->mark(kind)) return CKPT_E_HIP;         \
+    } while (0)
+
+int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost, uint8_t* arg,
+               void* workspace, Profile* prof) {
+    if (!chains || !cost || !arg || !workspace) return CKPT_E_ARG;
+    if (int rc = check_dims(L, M, B)) return rc;
+    if (!chains->uf || !chains->ub || !chains->wa || !chains->wabar) return CKPT_E_ARG;
+    if ((reinterpret_cast<uintptr_t>(cost) | reinterpret_cast<uintptr_t>(arg) |
+         reinterpret_cast<uintptr_t>(workspace)) & 255)
+        return CKPT_E_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int pitch = int(ckpt_row_pitch(M));
+    const int rows = int(ckpt_table_rows(L));
+    const Workspace ws = carve(workspace, L, B);
+
+    hipLaunchKernelGGL(precompute_kernel, dim3(B), dim3(64), 0, st, *chains, L, ws);
+    CKPT_AFTER_LAUNCH(CKPT_K_PRECOMPUTE);
+    const int mblocks = (M + 1 + 255) / 256;
+    for (int d = 0; d < L; ++d) {
+        hipLaunchKernelGGL(diag_kernel, dim3(mblocks, L - d, B), dim3(256), 0, st, *chains, L, M, pitch, rows,
+                           d, ws, cost, arg);
+        CKPT_AFTER_LAUNCH(CKPT_K_DIAG);
+    }
+    return CKPT_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -196,26 +241,36 @@ size_t ckpt_workspace_bytes(int L, int M, int B) {
 
 int ckpt_solve_batched(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
                        uint8_t* arg, void* workspace) {
-    if (!chains || !cost || !arg || !workspace) return CKPT_E_ARG;
-    if (int rc = check_dims(L, M, B)) return rc;
-    if (!chains->uf || !chains->ub || !chains->wa || !chains->wabar) return CKPT_E_ARG;
-    if ((reinterpret_cast<uintptr_t>(cost) | reinterpret_cast<uintptr_t>(arg) |
-         reinterpret_cast<uintptr_t>(workspace)) & 255)
-        return CKPT_E_ARG;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const int pitch = int(ckpt_row_pitch(M));
-    const int rows = int(ckpt_table_rows(L));
-    const Workspace ws = carve(workspace, L, B);
+    return solve_impl(chains, L, M, B, stream, cost, arg, workspace, nullptr);
+}
 
-    hipLaunchKernelGGL(precompute_kernel, dim3(B), dim3(64), 0, st, *chains, L, ws);
-    if (!hip_ok(hipGetLastError())) return CKPT_E_HIP;
-    const int mblocks = (M + 1 + 255) / 256;
-    for (int d = 0; d < L; ++d) {
-        hipLaunchKernelGGL(diag_kernel, dim3(mblocks, L - d, B), dim3(256), 0, st, *chains, L, M, pitch, rows,
-                           d, ws, cost, arg);
-        if (!hip_ok(hipGetLastError())) return CKPT_E_HIP;
+int ckpt_solve_profiled(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
+                        uint8_t* arg, void* workspace, float* kind_ms, int* kind_launches) {
+    if (!kind_ms || !kind_launches) return CKPT_E_ARG;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    Profile prof;
+    prof.stream = st;
+    for (int k = 0; k < CKPT_N_KERNEL_KINDS; ++k) kind_ms[k] = 0.f, kind_launches[k] = 0;
+    int rc = CKPT_OK;
+    if (!prof.mark(-1)) rc = CKPT_E_HIP;
+    if (rc == CKPT_OK) rc = solve_impl(chains, L, M, B, stream, cost, arg, workspace, &prof);
+    if (!hip_ok(hipStreamSynchronize(st)) && rc == CKPT_OK) rc = CKPT_E_HIP;
+    for (size_t i = 1; i < prof.events.size() && rc == CKPT_OK; ++i) {
+        float ms = 0.f;
+        if (!hip_ok(hipEventElapsedTime(&ms, prof.events[i - 1], prof.events[i]))) rc = CKPT_E_HIP;
+        kind_ms[prof.kinds[i]] += ms;
+        kind_launches[prof.kinds[i]] += 1;
     }
-    return CKPT_OK;
+    for (hipEvent_t e : prof.events) (void)hipEventDestroy(e);
+    return rc;
+}
+
+const char* ckpt_kernel_name(int kind) {
+    switch (kind) {
+        case CKPT_K_PRECOMPUTE: return "precompute_kernel";
+        case CKPT_K_DIAG: return "diag_kernel";
+        default: return nullptr;
+    }
 }
 
 int ckpt_check_inputs(const void* workspace, int L, int M, int B, void* stream, int32_t* flags_host) {
