@@ -59,7 +59,7 @@ extern "C" {
 enum {
     CKPT_OK = 0,
     CKPT_E_ARG = -1,        /* null pointer, L < 1, M < 0, B < 1, s/t/m out of range */
-    CKPT_E_LIMIT = -2,      /* L > CKPT_MAX_L, or a table larger than 2^31-1 rows*pitch per chain */
+    CKPT_E_LIMIT = -2,      /* L > CKPT_MAX_L, or rows*pitch >= 2^30 elements per chain */
     CKPT_E_INFEASIBLE = -3, /* ckpt_schedule: the requested cell is infeasible */
     CKPT_E_SMALLBUF = -4,   /* ckpt_schedule: ops_cap too small (2L-1 .. L(L+1)/2+L operations) */
     CKPT_E_HIP = -5,        /* a HIP call failed; see ckpt_last_hip_error() */
@@ -127,7 +127,7 @@ int ckpt_solve_batched(const ckpt_chains_t* chains, int L, int M, int B, void* s
  * Creates and destroys events (allocates); not for latency-critical callers.
  * Returns as ckpt_solve_batched.
  */
-enum { CKPT_K_PRECOMPUTE = 0, CKPT_K_DIAG = 1, CKPT_N_KERNEL_KINDS = 2 };
+enum { CKPT_K_PRECOMPUTE = 0, CKPT_K_GEMM = 1, CKPT_K_ROW = 2, CKPT_N_KERNEL_KINDS = 3 };
 int ckpt_solve_profiled(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
                         uint8_t* arg, void* workspace, float* kind_ms, int* kind_launches);
 /* Name of a kernel kind as it appears in a rocprofv3 kernel trace; NULL if out of range. */
@@ -155,6 +155,13 @@ int ckpt_check_inputs(const void* workspace, int L, int M, int B, void* stream, 
  */
 int ckpt_schedule(const uint8_t* arg_host, const int32_t* wa, const int32_t* wabar, int L, int M,
                   int s, int t, int m_budget, ckpt_op_t* ops_out, int ops_cap);
+
+/*
+ * Tuning knob: stage-block size of the fill (8 or 16; 0 = let the library choose).
+ * Process-wide, affects later ckpt_solve_* calls; results do not depend on it.
+ * Returns the previous value, or CKPT_E_ARG.
+ */
+int ckpt_set_tile(int T);
 
 /* hipError_t of the most recent failed HIP call made by this library (0 if none). */
 int ckpt_last_hip_error(void);

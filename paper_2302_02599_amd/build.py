@@ -11,7 +11,7 @@ LIB = os.path.join(HERE, "libckpt_dp.so")
 SOURCES = ["ckpt_dp.hip", "ckpt_schedule.cpp"]
 
 HIPCC_FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC", "-fno-honor-nans",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wall", "-Wno-unused-command-line-argument",
 ]

@@ -26,26 +26,59 @@ inline bool hip_ok(hipError_t e) {
 }
 
 // ---------------------------------------------------------------------------
-// Workspace layout (int32 units), all per chain b:
-//   P     [B][L+1]   P[i] = sum of u_f of stages 1..i
-//   fb    [B][L]     u_f^s + u_b^s
-//   mall  [B][L][L]  m_all^{s,t}  at [(s-1)*L + (t-1)]
-//   mnull [B][L][L]  m_null^{s,t}
-//   flags [B]        input precondition flags
+// How the table is filled
+//
+// Stages are 0-based inside this file: cell (i, j), 0 <= i <= j < L, is the paper's
+// (s, t) = (i + 1, j + 1).  A checkpoint split q in i+1..j is the paper's s' = q + 1:
+// left operand cell (i, q-1) at the same m, right operand cell (q, j) at m - omega_a^q,
+// plus the forward sweep P[q] - P[i] (C_ck of the Theorem).  Its candidate number is q + 1.
+//
+// Stages are grouped in blocks of T.  Tile (I, J) holds the cells with i in block I and
+// j in block J.  Tiles are processed by block diagonal D = J - I; within one D every
+// tile is independent.  The splits of a cell of tile (I, J), D >= 2, fall in three groups:
+//   middle   q in [(I+1)T, JT]: both operands lie in tiles of a smaller D.  This is a
+//            min-plus product of an 8x8 register tile per lane (gemm_kernel), where each
+//            loaded operand row is reused by 8 cells.
+//   near-i   q in block I: the right operand (q, j) is a lower row of the SAME tile, read
+//            at a shifted m, so rows must be finished bottom-up across launches.
+//   near-j   q in block J: the left operand (i, q-1) is an earlier cell of the same row at
+//            the same m, kept in registers.
+// row_kernel finishes one row r of every tile of the diagonal: near-i splits, then the
+// partial minimum of gemm_kernel, then near-j splits, then C_all and the two gates.
+// Launch order per D: gemm (D >= 2), then rows r = T-1 .. 0.
+//
+// Reads at m - shift are not bounds-checked against m < shift: a lane whose m is below
+// a shift of one of its splits is below m_null (m_all for C_all) of that cell, because
+// both thresholds contain every shift of the cell, so the gate discards whatever it
+// read.  Shifts are clamped to one row pitch, which keeps such reads inside the table.
 // ---------------------------------------------------------------------------
+
+// Workspace layout, all per chain b:
+//   P     [B][L+1] int32   P[i] = sum of u_f of stages 1..i
+//   fb    [B][L]   int32   min(2^30, u_f + u_b) of stage i+1
+//   wsh   [B][L]   int32   shift of split q: omega_a^q clamped to [0, pitch]
+//   wabs  [B][L]   int32   shift of C_all at row i: omega_abar^{i+1} clamped to [0, pitch]
+//   mall  [B][L][L] int32  m_all^{s,t}  at [i*L + j]
+//   mnull [B][L][L] int32  m_null^{s,t}
+//   flags [B]      int32   input precondition flags
+//   kq    [B][L]   double  P[q] + (q + 1) / 256: forward sweep up to split q, candidate number
+//                          in the fraction bits
 struct Workspace {
     int32_t* P;
     int32_t* fb;
+    int32_t* wsh;
+    int32_t* wabs;
     int32_t* mall;
     int32_t* mnull;
     int32_t* flags;
+    double* kq;
 };
 
 inline size_t align64(size_t n) { return (n + 63) & ~size_t(63); }
 
 inline size_t ws_ints(int L, int B) {
-    return align64(size_t(B) * (L + 1)) + align64(size_t(B) * L) + 2 * align64(size_t(B) * L * L) +
-           align64(size_t(B));
+    return align64(size_t(B) * (L + 1)) + 3 * align64(size_t(B) * L) + 2 * align64(size_t(B) * L * L) +
+           align64(size_t(B)) + 2 * align64(size_t(B) * L);
 }
 
 inline Workspace carve(void* base, int L, int B) {
@@ -53,20 +86,30 @@ inline Workspace carve(void* base, int L, int B) {
     Workspace w;
     w.P = p;      p += align64(size_t(B) * (L + 1));
     w.fb = p;     p += align64(size_t(B) * L);
+    w.wsh = p;    p += align64(size_t(B) * L);
+    w.wabs = p;   p += align64(size_t(B) * L);
     w.mall = p;   p += align64(size_t(B) * L * L);
     w.mnull = p;  p += align64(size_t(B) * L * L);
-    w.flags = p;
+    w.flags = p;  p += align64(size_t(B));
+    w.kq = reinterpret_cast<double*>(p);
     return w;
 }
 
-__host__ __device__ inline int tri_row(int L, int s0, int t0) {  // 0-based s0 <= t0
-    return s0 * L - (s0 * (s0 - 1)) / 2 + (t0 - s0);
+struct Ctx {
+    int L, M, pitch, rows;
+    Workspace ws;
+    int32_t* cost;
+    uint8_t* arg;
+};
+
+__host__ __device__ inline int tri_row(int L, int i, int j) {  // 0-based i <= j
+    return i * L - (i * (i - 1)) / 2 + (j - i);
 }
 
-// One block per chain.  Thread 0 builds the prefix sums and the flags; thread s0
-// builds row s of both threshold tables with a running maximum over t (last display
-// of the Theorem).
-__global__ void precompute_kernel(ckpt_chains_t ch, int L, Workspace ws) {
+// One block per chain.  Thread 0 builds the prefix sums and the flags; thread i builds
+// row i of both threshold tables with a running maximum over t (last display of the
+// Theorem).
+__global__ void precompute_kernel(ckpt_chains_t ch, int L, int pitch, Workspace ws) {
     const int b = blockIdx.x;
     const int32_t* uf = ch.uf + size_t(b) * L;
     const int32_t* ub = ch.ub + size_t(b) * L;
@@ -85,11 +128,14 @@ __global__ void precompute_kernel(ckpt_chains_t ch, int L, Workspace ws) {
             const int f = uf[k], bw = ub[k];
             if (f < 0 || bw < 0) flags |= 1;
             if (bw >= (1 << 30)) flags |= 2;
+            ws.kq[size_t(b) * L + k] = double(acc) + double(k + 1) * (1.0 / 256.0);
             acc += f > 0 ? f : 0;
             if (acc >= (1ll << 30)) { flags |= 2; acc = (1ll << 30) - 1; }
             P[k + 1] = static_cast<int32_t>(acc);
             ws.fb[size_t(b) * L + k] = static_cast<int32_t>(
                 min(static_cast<long long>(kInf), static_cast<long long>(f > 0 ? f : 0) + (bw > 0 ? bw : 0)));
+            ws.wsh[size_t(b) * L + k] = min(max(wa[k], 0), pitch);
+            ws.wabs[size_t(b) * L + k] = min(max(wab[k], 0), pitch);
             const int sizes[5] = {wa[k + 1], wab[k], wd[k + 1], of ? of[k] : 0, ob ? ob[k] : 0};
             for (int v : sizes) {
                 if (v < 0) flags |= 1;
@@ -105,7 +151,7 @@ __global__ void precompute_kernel(ckpt_chains_t ch, int L, Workspace ws) {
     for (int s0 = threadIdx.x; s0 < L; s0 += blockDim.x) {
         const int s = s0 + 1;
         const int ofs = of ? sz(of[s0]) : 0, obs = ob ? sz(ob[s0]) : 0;
-        int sweep = sz(wa[s]) + ofs;  // wa^s + o_f^s, then max over s+1 <= j < t
+        int sweep = sz(wa[s]) + ofs;  // omega_a^s + o_f^s, then max over s+1 <= j < t
         int32_t* mall = ws.mall + (size_t(b) * L + s0) * L;
         int32_t* mnull = ws.mnull + (size_t(b) * L + s0) * L;
         for (int t = s; t <= L; ++t) {
@@ -119,56 +165,210 @@ __global__ void precompute_kernel(ckpt_chains_t ch, int L, Workspace ws) {
     }
 }
 
-// Reference-shaped fill of one anti-diagonal d = t - s: one thread per (chain, s, m),
-// serial loop over the split point.  Operands come straight from global memory.
-__global__ void __launch_bounds__(256)
-diag_kernel(ckpt_chains_t ch, int L, int M, int pitch, int rows, int d, Workspace ws,
-            int32_t* __restrict__ cost, uint8_t* __restrict__ arg) {
-    const int b = blockIdx.z;
-    const int s0 = blockIdx.y;  // 0-based stage s-1
-    const int t0 = s0 + d;
-    const int m = blockIdx.x * blockDim.x + threadIdx.x;
-    if (m > M) return;
-    const int32_t* wa = ch.wa + size_t(b) * (L + 1);
-    const int32_t* wab = ch.wabar + size_t(b) * L;
-    const int32_t* P = ws.P + size_t(b) * (L + 1);
-    const int32_t* tab = cost + size_t(b) * rows * pitch;
-    const uint32_t mall = ws.mall[(size_t(b) * L + s0) * L + t0];
-    const uint32_t mnull = ws.mnull[(size_t(b) * L + s0) * L + t0];
-    const uint32_t fb = ws.fb[size_t(b) * L + s0];
+// Table reads go through a raw buffer descriptor of the chain's cost table: the address
+// is descriptor base + per-lane byte offset (vector register, fixed for the whole kernel)
+// + wave-uniform byte offset of the row (scalar register), so no vector instruction is
+// spent on addressing, and a read outside the chain's table returns 0 instead of faulting.
+// The scalar offset is 32-bit: a chain's table must stay below 4 GiB (checked on the host).
+using rsrc_t = __amdgpu_buffer_rsrc_t;
 
-    uint32_t best = kInf;
-    uint32_t pick = 0;
-    if (uint32_t(m) >= mall) {
-        uint32_t v = fb;
-        if (d > 0) {
-            const int mm = m - min(max(wab[s0], 0), pitch);
-            v += (mm >= 0) ? uint32_t(tab[size_t(tri_row(L, s0 + 1, t0)) * pitch + mm]) : kInf;
-        }
-        v = min(v, kInf);
-        if (v < best) { best = v; pick = s0 + 1; }
-    }
-    if (d > 0 && uint32_t(m) >= mnull) {
-        const int32_t* left = tab + size_t(tri_row(L, s0, s0)) * pitch + m;  // rows (s, s..t-1)
-        const uint32_t Ps = P[s0];
-        for (int q0 = s0 + 1; q0 <= t0; ++q0) {  // q0 = 0-based s'-1 ... candidate stage s' = q0 + 1
-            const int mm = m - min(max(wa[q0], 0), pitch);
-            const uint32_t r = (mm >= 0) ? uint32_t(tab[size_t(tri_row(L, q0, t0)) * pitch + mm]) : kInf;
-            const uint32_t l = uint32_t(left[size_t(q0 - 1 - s0) * pitch]);
-            const uint32_t v = min(uint32_t(P[q0]) - Ps + r + l, kInf);
-            if (v < best) { best = v; pick = q0 + 1; }
-        }
-    }
-    const size_t o = (size_t(b) * rows + tri_row(L, s0, t0)) * pitch + m;
-    cost[o] = int32_t(best);
-    arg[o] = uint8_t(pick);
+__device__ __forceinline__ rsrc_t table_rsrc(const int32_t* tab, uint32_t bytes) {
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<int32_t*>(tab), 0, int(bytes), 0x00020000);
 }
+
+__device__ __forceinline__ uint32_t ld32(rsrc_t tab, uint32_t elem, uint32_t off) {
+    return uint32_t(__builtin_amdgcn_raw_buffer_load_b32(tab, int(off), int(elem << 2), 0));
+}
+
+// Middle splits of every tile of block diagonal D >= 2 (also correct for D = 1).
+// One wave owns an 8x8 sub-tile of cells for 64 consecutive m; lane = m.  For T = 16 the
+// four waves of a work-group cover the 16x16 tile and share operand rows through L1/L2.
+// Candidates are compared as float64 keys  cost + (q+1)/256 : one add and one min per
+// candidate give the minimum cost and, among equal costs, the smallest candidate number
+// (all values are integers below 2^34 scaled by 2^-8, exact in float64).
+// Output: cost[] <- unsaturated partial minimum, arg[] <- its candidate number.
+template <int T>
+__global__ void __launch_bounds__(64 * (T / 8) * (T / 8), 2) gemm_kernel(Ctx c, int D) {
+    constexpr int W = T / 8;
+    constexpr int NB = 3;  // operand buffers in flight: loads run two splits ahead
+    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
+    const int rw = wave / W, cw = wave % W;
+    const int b = blockIdx.z, I = blockIdx.y, J = I + D;
+    const int L = c.L, pitch = c.pitch;
+    const int j0 = J * T + cw * 8;
+    if (j0 >= L) return;  // ragged last block: this sub-tile has no column
+    const int i0 = I * T + rw * 8;
+    const uint32_t m = blockIdx.x * 64 + (threadIdx.x & 63);
+    const uint32_t moff = m * 4;
+    const size_t chain = size_t(b) * c.rows * pitch;
+    const rsrc_t tab = table_rsrc(c.cost + chain, uint32_t(c.rows) * uint32_t(pitch) * 4u);
+    const int32_t* wsh = c.ws.wsh + size_t(b) * L;
+    const double* kq = c.ws.kq + size_t(b) * L;
+    const int qlo = (I + 1) * T, qhi = J * T;
+
+    int lrow0[8], jcol[8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) lrow0[r] = tri_row(L, i0 + r, i0 + r) - (i0 + r) - 1;  // + q = row of (i, q-1)
+#pragma unroll
+    for (int cc = 0; cc < 8; ++cc) jcol[cc] = min(j0 + cc, L - 1);
+
+    double key[8][8];
+#pragma unroll
+    for (int r = 0; r < 8; ++r)
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc) key[r][cc] = 0x1p60;
+
+    uint32_t buf[NB][16];
+    auto load = [&](uint32_t(&v)[16], int q) {
+        const int rq = q * L - (q * (q - 1)) / 2 - q;  // + j = row of (q, j)
+        const int sh = wsh[q];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) v[r] = ld32(tab, uint32_t(lrow0[r] + q) * uint32_t(pitch), moff);
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc)
+            v[8 + cc] = ld32(tab, uint32_t(rq + jcol[cc]) * uint32_t(pitch) - uint32_t(sh), moff);
+    };
+    auto compute = [&](const uint32_t(&v)[16], int q) {
+        const double cq = kq[q];
+        double lk[8], rk[8];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) lk[r] = double(v[r]);
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc) rk[cc] = double(v[8 + cc]) + cq;
+#pragma unroll
+        for (int r = 0; r < 8; ++r)
+#pragma unroll
+            for (int cc = 0; cc < 8; ++cc) key[r][cc] = fmin(key[r][cc], lk[r] + rk[cc]);
+    };
+
+    // Straight-line pipeline: the split list is padded to a multiple of NB by repeating the
+    // last split (a repeated candidate cannot change a minimum), so the loop body has no
+    // branches and the loads of split q + 2 are in flight while split q is evaluated.
+#pragma unroll
+    for (int u = 0; u < NB - 1; ++u) load(buf[u], min(qlo + u, qhi));
+    const int iters = (qhi - qlo + NB) / NB;
+    int q = qlo;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < NB; ++u) {
+            load(buf[(u + NB - 1) % NB], min(q + NB - 1, qhi));
+            compute(buf[u], min(q, qhi));
+            ++q;
+        }
+    }
+
+    const int32_t* P = c.ws.P + size_t(b) * (L + 1);
+#pragma unroll
+    for (int r = 0; r < 8; ++r) {
+        const uint32_t Pi = P[i0 + r];
+        const size_t row = chain + size_t(tri_row(L, i0 + r, j0)) * pitch + m;
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc) {
+            if (j0 + cc < L) {
+                const double k = fmin(key[r][cc], 0x1p33);
+                const double fl = floor(k);
+                c.cost[row + size_t(cc) * pitch] = int32_t(uint32_t(fl) - Pi);
+                c.arg[row + size_t(cc) * pitch] = uint8_t(uint32_t((k - fl) * 256.0));
+            }
+        }
+    }
+}
+
+// Finishes row r of every tile of block diagonal D: cells (i, j), i = I*T + r, j in block
+// J = I + D.  One lane per m.  Candidate order = candidate number order, strict '<' keeps
+// the smallest number among equal costs: near-i splits, gemm partial, near-j splits; C_all
+// (number i + 1, the smallest) wins ties at the end.
+template <int T>
+__global__ void __launch_bounds__(256) row_kernel(Ctx c, int D, int r) {
+    const int b = blockIdx.z, I = blockIdx.y, J = I + D;
+    const int L = c.L, pitch = c.pitch;
+    const int i = I * T + r;
+    if (i >= L) return;
+    const uint32_t m = blockIdx.x * 256 + threadIdx.x;
+    if (m >= uint32_t(pitch)) return;
+    const uint32_t moff = m * 4;
+    const size_t chain = size_t(b) * c.rows * pitch;
+    const rsrc_t tab = table_rsrc(c.cost + chain, uint32_t(c.rows) * uint32_t(pitch) * 4u);
+    const int32_t* P = c.ws.P + size_t(b) * (L + 1);
+    const int32_t* wsh = c.ws.wsh + size_t(b) * L;
+    const int32_t* mall = c.ws.mall + (size_t(b) * L + i) * L;
+    const int32_t* mnull = c.ws.mnull + (size_t(b) * L + i) * L;
+    const int jb = J * T;
+    const int cend = min(T, L - jb);      // columns of this tile that exist
+    const int cfirst = (D == 0) ? r : 0;  // first column with j >= i
+    const uint32_t Pi = P[i];
+    const uint32_t fbi = c.ws.fb[size_t(b) * L + i];
+    const int wabi = c.ws.wabs[size_t(b) * L + i];
+    const int rowi = tri_row(L, i, i) - i;  // + j = row of (i, j)
+
+    uint32_t best[T], pick[T], val[T];
+#pragma unroll
+    for (int cc = 0; cc < T; ++cc) best[cc] = 0xffffffffu, pick[cc] = 0, val[cc] = kInf;
+
+    // near-i splits (and, for D = 1, the single middle split q = jb)
+    const int q_end = (D == 0) ? i : (D == 1 ? jb : (I + 1) * T - 1);
+    for (int q = i + 1; q <= q_end; ++q) {
+        const uint32_t lb = ld32(tab, uint32_t(rowi + q - 1) * uint32_t(pitch), moff) + (uint32_t(P[q]) - Pi);
+        const int rq = q * L - (q * (q - 1)) / 2 - q;
+        const int sh = wsh[q];
+#pragma unroll
+        for (int cc = 0; cc < T; ++cc) {
+            const int j = min(jb + cc, L - 1);
+            const uint32_t v = lb + ld32(tab, uint32_t(rq + j) * uint32_t(pitch) - uint32_t(sh), moff);
+            if (v < best[cc]) best[cc] = v, pick[cc] = q + 1;
+        }
+    }
+    // partial minimum over the middle splits
+    if (D >= 2) {
+#pragma unroll
+        for (int cc = 0; cc < T; ++cc) {
+            const int j = min(jb + cc, L - 1);
+            const size_t o = chain + size_t(rowi + j) * pitch + m;
+            const uint32_t v = uint32_t(c.cost[o]);
+            const uint32_t pk = c.arg[o];
+            if (v < best[cc]) best[cc] = v, pick[cc] = pk;
+        }
+    }
+    // near-j splits, gates and C_all, left to right
+#pragma unroll
+    for (int cc = 0; cc < T; ++cc) {
+        if (cc >= cfirst && cc < cend) {
+            const int j = jb + cc;
+#pragma unroll
+            for (int c2 = 0; c2 < cc; ++c2) {
+                if (c2 >= cfirst) {
+                    const int q = jb + c2 + 1;  // left operand (i, q-1) = val[c2]
+                    const int rq = q * L - (q * (q - 1)) / 2 - q;
+                    const uint32_t v = val[c2] + (uint32_t(P[q]) - Pi) +
+                                       ld32(tab, uint32_t(rq + j) * uint32_t(pitch) - uint32_t(wsh[q]), moff);
+                    if (v < best[cc]) best[cc] = v, pick[cc] = q + 1;
+                }
+            }
+            const uint32_t ck = (m >= uint32_t(mnull[j])) ? min(best[cc], kInf) : kInf;
+            uint32_t all = fbi;
+            if (j > i) {
+                const int rq = (i + 1) * L - ((i + 1) * i) / 2 - (i + 1);
+                all += ld32(tab, uint32_t(rq + j) * uint32_t(pitch) - uint32_t(wabi), moff);
+            }
+            all = (m >= uint32_t(mall[j])) ? min(all, kInf) : kInf;
+            const bool take_all = all < kInf && all <= ck;
+            const uint32_t fin = take_all ? all : ck;
+            const uint32_t fpk = take_all ? uint32_t(i + 1) : (ck < kInf ? pick[cc] : 0u);
+            val[cc] = fin;
+            const size_t o = chain + size_t(rowi + j) * pitch + m;
+            c.cost[o] = int32_t(fin);
+            c.arg[o] = uint8_t(fpk);
+        }
+    }
+}
+
+std::atomic<int> g_tile{0};  // 0 = choose automatically
 
 int check_dims(int L, int M, int B) {
     if (L < 1 || M < 0 || B < 1) return CKPT_E_ARG;
     if (L > CKPT_MAX_L) return CKPT_E_LIMIT;
     const unsigned long long per_chain = (unsigned long long)ckpt_table_rows(L) * ckpt_row_pitch(M);
-    if (per_chain > 0x7fffffffull) return CKPT_E_LIMIT;
+    if (per_chain >= (1ull << 30)) return CKPT_E_LIMIT;  // 4 GiB of int32 per chain
     return CKPT_OK;
 }
 
@@ -205,13 +405,29 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     const int rows = int(ckpt_table_rows(L));
     const Workspace ws = carve(workspace, L, B);
 
-    hipLaunchKernelGGL(precompute_kernel, dim3(B), dim3(64), 0, st, *chains, L, ws);
+    hipLaunchKernelGGL(precompute_kernel, dim3(B), dim3(64), 0, st, *chains, L, pitch, ws);
     CKPT_AFTER_LAUNCH(CKPT_K_PRECOMPUTE);
-    const int mblocks = (M + 1 + 255) / 256;
-    for (int d = 0; d < L; ++d) {
-        hipLaunchKernelGGL(diag_kernel, dim3(mblocks, L - d, B), dim3(256), 0, st, *chains, L, M, pitch, rows,
-                           d, ws, cost, arg);
-        CKPT_AFTER_LAUNCH(CKPT_K_DIAG);
+    const Ctx ctx{L, M, pitch, rows, ws, cost, arg};
+    int T = g_tile.load();
+    if (T != 8 && T != 16) T = 8;
+    const int nblk = (L + T - 1) / T;
+    const int gx_gemm = pitch / 64, gx_row = (pitch + 255) / 256;
+    for (int D = 0; D < nblk; ++D) {
+        const dim3 tiles_gemm(gx_gemm, nblk - D, B), tiles_row(gx_row, nblk - D, B);
+        if (D >= 2) {
+            if (T == 8)
+                hipLaunchKernelGGL(gemm_kernel<8>, tiles_gemm, dim3(64), 0, st, ctx, D);
+            else
+                hipLaunchKernelGGL(gemm_kernel<16>, tiles_gemm, dim3(256), 0, st, ctx, D);
+            CKPT_AFTER_LAUNCH(CKPT_K_GEMM);
+        }
+        for (int r = T - 1; r >= 0; --r) {
+            if (T == 8)
+                hipLaunchKernelGGL(row_kernel<8>, tiles_row, dim3(256), 0, st, ctx, D, r);
+            else
+                hipLaunchKernelGGL(row_kernel<16>, tiles_row, dim3(256), 0, st, ctx, D, r);
+            CKPT_AFTER_LAUNCH(CKPT_K_ROW);
+        }
     }
     return CKPT_OK;
 }
@@ -268,7 +484,8 @@ int ckpt_solve_profiled(const ckpt_chains_t* chains, int L, int M, int B, void* 
 const char* ckpt_kernel_name(int kind) {
     switch (kind) {
         case CKPT_K_PRECOMPUTE: return "precompute_kernel";
-        case CKPT_K_DIAG: return "diag_kernel";
+        case CKPT_K_GEMM: return "gemm_kernel";
+        case CKPT_K_ROW: return "row_kernel";
         default: return nullptr;
     }
 }
@@ -287,6 +504,11 @@ int ckpt_check_inputs(const void* workspace, int L, int M, int B, void* stream, 
 }
 
 int ckpt_last_hip_error(void) { return g_last_hip_error.load(); }
+
+int ckpt_set_tile(int T) {
+    if (T != 0 && T != 8 && T != 16) return CKPT_E_ARG;
+    return g_tile.exchange(T);
+}
 
 const char* ckpt_strerror(int code) {
     switch (code) {

@@ -10,15 +10,20 @@ from persistent_bruteforce import simulate
 from workloads import ChainBatch, make_config, random_chain_batch
 
 pytestmark = pytest.mark.gpu
+_full = {}
 
 
-@pytest.fixture(scope="module")
-def amd():
+@pytest.fixture(scope="module", params=[8, 16], ids=["tile8", "tile16"])
+def amd(request):
+    """The library, once per stage-block size of the fill (results must not depend on it)."""
     import torch
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     import paper_2302_02599_amd as amd
     amd.load_library()          # raises if the HIP library is not built: there is no fallback
-    return amd
+    _full.clear()
+    amd.ckpt_set_tile(request.param)
+    yield amd
+    amd.ckpt_set_tile(0)
 
 
 @pytest.mark.parametrize("cfg", [0, 1, 2])
@@ -36,6 +41,8 @@ def test_configs_small(amd, oracle_mod, cfg):
     (16, 255, 2, 9, False, False, False), (17, 256, 3, 10, True, True, True),
     (23, 300, 2, 11, True, True, False), (31, 513, 2, 12, False, True, False),
     (33, 97, 5, 13, True, False, False), (40, 1, 2, 14, False, False, False),
+    (50, 130, 2, 15, True, True, False), (57, 66, 3, 16, False, False, False), (71, 190, 1, 17, True, True, False),
+    (64, 64, 2, 18, False, True, False), (100, 70, 1, 19, True, False, False),
 ])
 def test_ragged_shapes(amd, oracle_mod, L, M, B, seed, ovh, wd, zero):
     """Chain lengths and budgets that are not multiples of any tile, incl. M = 0 and L = 1."""
@@ -133,9 +140,6 @@ def test_solve_on_a_side_stream(amd, oracle_mod):
         sol = amd.solve(batch)
     st.synchronize()
     assert_tables_equal(oracle_mod, batch, sol)
-
-
-_full = {}
 
 
 def _full_solution(amd, cfg):
