@@ -189,24 +189,46 @@ __device__ __forceinline__ uint32_t ld32(rsrc_t tab, uint32_t elem, uint32_t off
 // candidate give the minimum cost and, among equal costs, the smallest candidate number
 // (all values are integers below 2^34 scaled by 2^-8, exact in float64).
 // Output: cost[] <- unsaturated partial minimum, arg[] <- its candidate number.
-template <int T>
+template <int T, int NB, int UNR>
 __global__ void __launch_bounds__(64 * (T / 8) * (T / 8), 2) gemm_kernel(Ctx c, int D) {
+    constexpr bool XCD = false;
     constexpr int W = T / 8;
-    constexpr int NB = 3;  // operand buffers in flight: loads run two splits ahead
+    // NB operand buffers in flight: loads run NB-1 splits ahead
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
     const int rw = wave / W, cw = wave % W;
-    const int b = blockIdx.z, I = blockIdx.y, J = I + D;
+    int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
+    if (XCD) {
+        // Work-groups go round-robin to the 8 XCDs in dispatch order.  Renumber them so that
+        // each XCD works on a contiguous range of (chain, tile, m-chunk).
+        const uint32_t n = gridDim.x * gridDim.y * gridDim.z;
+        const uint32_t id = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+        const uint32_t per = n / 8, main = per * 8;
+        const uint32_t lid = id < main ? (id % 8) * per + id / 8 : id;
+        bx = lid % gridDim.x;
+        by = (lid / gridDim.x) % gridDim.y;
+        bz = lid / (gridDim.x * gridDim.y);
+    }
+    const int b = bz, I = by, J = I + D;
     const int L = c.L, pitch = c.pitch;
+    const int qlo = (I + 1) * T, qhi = J * T;
+
+    // Per-split constants (shift, key offset) go through LDS once: a scalar memory load per
+    // split would put its full latency on the critical path of every pipeline step.
+    __shared__ double s_kq[CKPT_MAX_L + 2];
+    __shared__ int32_t s_sh[CKPT_MAX_L + 2];
+    for (int k = threadIdx.x; k <= qhi - qlo; k += blockDim.x) {
+        s_kq[k] = c.ws.kq[size_t(b) * L + qlo + k];
+        s_sh[k] = c.ws.wsh[size_t(b) * L + qlo + k];
+    }
+    __syncthreads();
+
     const int j0 = J * T + cw * 8;
     if (j0 >= L) return;  // ragged last block: this sub-tile has no column
     const int i0 = I * T + rw * 8;
-    const uint32_t m = blockIdx.x * 64 + (threadIdx.x & 63);
+    const uint32_t m = bx * 64 + (threadIdx.x & 63);
     const uint32_t moff = m * 4;
     const size_t chain = size_t(b) * c.rows * pitch;
     const rsrc_t tab = table_rsrc(c.cost + chain, uint32_t(c.rows) * uint32_t(pitch) * 4u);
-    const int32_t* wsh = c.ws.wsh + size_t(b) * L;
-    const double* kq = c.ws.kq + size_t(b) * L;
-    const int qlo = (I + 1) * T, qhi = J * T;
 
     int lrow0[8], jcol[8];
 #pragma unroll
@@ -223,7 +245,7 @@ __global__ void __launch_bounds__(64 * (T / 8) * (T / 8), 2) gemm_kernel(Ctx c, 
     uint32_t buf[NB][16];
     auto load = [&](uint32_t(&v)[16], int q) {
         const int rq = q * L - (q * (q - 1)) / 2 - q;  // + j = row of (q, j)
-        const int sh = wsh[q];
+        const int sh = __builtin_amdgcn_readfirstlane(s_sh[q - qlo]);
 #pragma unroll
         for (int r = 0; r < 8; ++r) v[r] = ld32(tab, uint32_t(lrow0[r] + q) * uint32_t(pitch), moff);
 #pragma unroll
@@ -231,7 +253,7 @@ __global__ void __launch_bounds__(64 * (T / 8) * (T / 8), 2) gemm_kernel(Ctx c, 
             v[8 + cc] = ld32(tab, uint32_t(rq + jcol[cc]) * uint32_t(pitch) - uint32_t(sh), moff);
     };
     auto compute = [&](const uint32_t(&v)[16], int q) {
-        const double cq = kq[q];
+        const double cq = s_kq[q - qlo];
         double lk[8], rk[8];
 #pragma unroll
         for (int r = 0; r < 8; ++r) lk[r] = double(v[r]);
@@ -248,13 +270,16 @@ __global__ void __launch_bounds__(64 * (T / 8) * (T / 8), 2) gemm_kernel(Ctx c, 
     // branches and the loads of split q + 2 are in flight while split q is evaluated.
 #pragma unroll
     for (int u = 0; u < NB - 1; ++u) load(buf[u], min(qlo + u, qhi));
-    const int iters = (qhi - qlo + NB) / NB;
+    constexpr int STEPS = NB * UNR;  // pipeline steps per loop iteration
+    const int iters = (qhi - qlo + STEPS) / STEPS;
     int q = qlo;
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int u = 0; u < NB; ++u) {
+        for (int u = 0; u < STEPS; ++u) {
             load(buf[(u + NB - 1) % NB], min(q + NB - 1, qhi));
-            compute(buf[u], min(q, qhi));
+            __builtin_amdgcn_sched_barrier(0);  // keep the loads of split q+NB-1 ahead of the math of split q
+            compute(buf[u % NB], min(q, qhi));
+            __builtin_amdgcn_sched_barrier(0);
             ++q;
         }
     }
@@ -454,7 +479,12 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     for (int D = 0; D < nblk; ++D) {
         const dim3 tiles_gemm(gx_gemm, nblk - D, B), tiles_row(gx_row, nblk - D, B);
         if (D >= 2) {
-            hipLaunchKernelGGL(gemm_kernel<T>, tiles_gemm, dim3(64), 0, st, ctx, D);
+            switch (g_tile.load()) {  // experiment selector
+                case 1: hipLaunchKernelGGL((gemm_kernel<T, 3, 2>), tiles_gemm, dim3(64), 0, st, ctx, D); break;
+                case 2: hipLaunchKernelGGL((gemm_kernel<T, 3, 3>), tiles_gemm, dim3(64), 0, st, ctx, D); break;
+                case 3: hipLaunchKernelGGL((gemm_kernel<T, 2, 4>), tiles_gemm, dim3(64), 0, st, ctx, D); break;
+                default: hipLaunchKernelGGL((gemm_kernel<T, 3, 1>), tiles_gemm, dim3(64), 0, st, ctx, D); break;
+            }
             CKPT_AFTER_LAUNCH(CKPT_K_GEMM);
         }
         const auto& rowfn = D == 0 ? kRow0 : (D == 1 ? kRow1 : kRow2);
@@ -540,7 +570,7 @@ int ckpt_check_inputs(const void* workspace, int L, int M, int B, void* stream, 
 int ckpt_last_hip_error(void) { return g_last_hip_error.load(); }
 
 int ckpt_set_tile(int T) {
-    if (T != 0 && T != 8 && T != 16) return CKPT_E_ARG;
+    if (T < 0 || T > 16) return CKPT_E_ARG;
     return g_tile.exchange(T);
 }
 
