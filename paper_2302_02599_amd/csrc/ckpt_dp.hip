@@ -17,6 +17,7 @@
 namespace {
 
 constexpr uint32_t kInf = 1u << 30;
+constexpr int kT = 8;  // stage-block size of the fill
 std::atomic<int> g_last_hip_error{0};
 
 inline bool hip_ok(hipError_t e) {
@@ -63,6 +64,7 @@ inline bool hip_ok(hipError_t e) {
 //   mall  [B][L][L] int32  m_all^{s,t}  at [i*L + j]
 //   mnull [B][L][L] int32  m_null^{s,t}
 //   flags [B]      int32   input precondition flags
+//   need  [B][L][L] int32  feasibility frontier: smallest m at which cell (i, j) can be finite
 //   kq    [B][L]   double  P[q] + (q + 1) / 256: forward sweep up to split q, candidate number
 //                          in the fraction bits
 struct Workspace {
@@ -73,13 +75,14 @@ struct Workspace {
     int32_t* mall;
     int32_t* mnull;
     int32_t* flags;
+    int32_t* need;
     double* kq;
 };
 
 inline size_t align64(size_t n) { return (n + 63) & ~size_t(63); }
 
 inline size_t ws_ints(int L, int B) {
-    return align64(size_t(B) * (L + 1)) + 3 * align64(size_t(B) * L) + 2 * align64(size_t(B) * L * L) +
+    return align64(size_t(B) * (L + 1)) + 3 * align64(size_t(B) * L) + 3 * align64(size_t(B) * L * L) +
            align64(size_t(B)) + 2 * align64(size_t(B) * L);
 }
 
@@ -93,6 +96,7 @@ inline Workspace carve(void* base, int L, int B) {
     w.mall = p;   p += align64(size_t(B) * L * L);
     w.mnull = p;  p += align64(size_t(B) * L * L);
     w.flags = p;  p += align64(size_t(B));
+    w.need = p;   p += align64(size_t(B) * L * L);
     w.kq = reinterpret_cast<double*>(p);
     return w;
 }
@@ -108,11 +112,18 @@ __host__ __device__ inline int tri_row(int L, int i, int j) {  // 0-based i <= j
     return i * L - (i * (i - 1)) / 2 + (j - i);
 }
 
-// One block per chain.  Thread 0 builds the prefix sums and the flags; thread i builds
-// row i of both threshold tables with a running maximum over t (last display of the
-// Theorem).
-__global__ void precompute_kernel(ckpt_chains_t ch, int L, int pitch, Workspace ws) {
+// One block per chain: input checks, prefix sums, shifts, both threshold tables (last
+// display of the Theorem) and the feasibility frontier need[i][j] = smallest m at which
+// cell (i, j) can be finite.
+//
+// The frontier follows the recurrence with costs dropped: a leaf needs m_all; keeping
+// abar^s needs max(m_all, omega_abar^s + need(s+1, t)); a checkpoint split at q needs
+// max(m_null, omega_a^q + need(q, t), need(s, q-1)).  A cell below its frontier is
+// infeasible whatever the times are, so the fill kernels skip work there.  Values
+// saturate at 2^30, above any admissible M.
+__global__ void __launch_bounds__(1024) precompute_kernel(ckpt_chains_t ch, int L, int pitch, Workspace ws) {
     const int b = blockIdx.x;
+    const int tid = threadIdx.x;
     const int32_t* uf = ch.uf + size_t(b) * L;
     const int32_t* ub = ch.ub + size_t(b) * L;
     const int32_t* wa = ch.wa + size_t(b) * (L + 1);
@@ -120,37 +131,49 @@ __global__ void precompute_kernel(ckpt_chains_t ch, int L, int pitch, Workspace 
     const int32_t* wd = ch.wdelta ? ch.wdelta + size_t(b) * (L + 1) : wa;
     const int32_t* of = ch.of ? ch.of + size_t(b) * L : nullptr;
     const int32_t* ob = ch.ob ? ch.ob + size_t(b) * L : nullptr;
+    __shared__ int s_flags;
+    __shared__ int32_t s_uf[CKPT_MAX_L + 2];
+    if (tid == 0) s_flags = 0;
+    __syncthreads();
 
-    if (threadIdx.x == 0) {
+    // Sizes are clamped into [0, 2^28] so that thresholds of a bad chain cannot overflow.
+    auto sz = [](int v) { return min(max(v, 0), 1 << 28); };
+    for (int k = tid; k < L; k += blockDim.x) {
+        const int f = uf[k], bw = ub[k];
         int flags = 0;
+        if (f < 0 || bw < 0) flags |= 1;
+        if (f >= (1 << 30) || bw >= (1 << 30)) flags |= 2;
+        const int fc = min(max(f, 0), (1 << 30) - 1), bc = min(max(bw, 0), 1 << 30);
+        s_uf[k] = fc;
+        ws.fb[size_t(b) * L + k] = int32_t(min(kInf, uint32_t(fc) + uint32_t(bc)));
+        ws.wsh[size_t(b) * L + k] = min(max(wa[k], 0), pitch);
+        ws.wabs[size_t(b) * L + k] = min(max(wab[k], 0), pitch);
+        const int sizes[5] = {wa[k + 1], wab[k], wd[k + 1], of ? of[k] : 0, ob ? ob[k] : 0};
+        for (int v : sizes) {
+            if (v < 0) flags |= 1;
+            if (v > (1 << 28)) flags |= 4;
+        }
+        if (k == 0) {
+            if (wa[0] < 0 || wd[0] < 0) flags |= 1;
+            if (wa[0] > (1 << 28) || wd[0] > (1 << 28)) flags |= 4;
+        }
+        if (flags) atomicOr(&s_flags, flags);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int flags = s_flags;
         long long acc = 0;
         int32_t* P = ws.P + size_t(b) * (L + 1);
         P[0] = 0;
         for (int k = 0; k < L; ++k) {
-            const int f = uf[k], bw = ub[k];
-            if (f < 0 || bw < 0) flags |= 1;
-            if (bw >= (1 << 30)) flags |= 2;
             ws.kq[size_t(b) * L + k] = double(acc) + double(k + 1) * (1.0 / 256.0);
-            acc += f > 0 ? f : 0;
+            acc += s_uf[k];
             if (acc >= (1ll << 30)) { flags |= 2; acc = (1ll << 30) - 1; }
-            P[k + 1] = static_cast<int32_t>(acc);
-            ws.fb[size_t(b) * L + k] = static_cast<int32_t>(
-                min(static_cast<long long>(kInf), static_cast<long long>(f > 0 ? f : 0) + (bw > 0 ? bw : 0)));
-            ws.wsh[size_t(b) * L + k] = min(max(wa[k], 0), pitch);
-            ws.wabs[size_t(b) * L + k] = min(max(wab[k], 0), pitch);
-            const int sizes[5] = {wa[k + 1], wab[k], wd[k + 1], of ? of[k] : 0, ob ? ob[k] : 0};
-            for (int v : sizes) {
-                if (v < 0) flags |= 1;
-                if (v > (1 << 28)) flags |= 4;
-            }
+            P[k + 1] = int32_t(acc);
         }
-        if (wa[0] < 0 || wd[0] < 0) flags |= 1;
-        if (wa[0] > (1 << 28) || wd[0] > (1 << 28)) flags |= 4;
         ws.flags[b] = flags;
     }
-    // Clamp sizes into [0, 2^28] so that thresholds of a bad chain cannot overflow.
-    auto sz = [](int v) { return min(max(v, 0), 1 << 28); };
-    for (int s0 = threadIdx.x; s0 < L; s0 += blockDim.x) {
+    for (int s0 = tid; s0 < L; s0 += blockDim.x) {
         const int s = s0 + 1;
         const int ofs = of ? sz(of[s0]) : 0, obs = ob ? sz(ob[s0]) : 0;
         int sweep = sz(wa[s]) + ofs;  // omega_a^s + o_f^s, then max over s+1 <= j < t
@@ -164,6 +187,48 @@ __global__ void precompute_kernel(ckpt_chains_t ch, int L, int pitch, Workspace 
             mall[t - 1] = max(sz(wd[t]) + sz(wab[s0]) + ofs, sz(wd[s]) + sz(wab[s0]) + obs);
             mnull[t - 1] = sz(wd[t]) + sweep;
         }
+    }
+    __syncthreads();
+
+    // Feasibility frontier, one segment length at a time.  The triangle lives in LDS (row-major
+    // packed, L(L+1)/2 ints <= 127 KiB); 16 lanes share the splits of one cell.
+    extern __shared__ int32_t s_need[];
+    __shared__ int32_t s_wa[CKPT_MAX_L + 2];
+    __shared__ int32_t s_wab[CKPT_MAX_L + 2];
+    for (int k = tid; k <= L; k += blockDim.x) s_wa[k] = sz(wa[k]);
+    for (int k = tid; k < L; k += blockDim.x) s_wab[k] = sz(wab[k]);
+    int32_t* need = ws.need + size_t(b) * L * L;
+    const int32_t* mallb = ws.mall + size_t(b) * L * L;
+    const int32_t* mnullb = ws.mnull + size_t(b) * L * L;
+    constexpr int kSat = 1 << 30;
+    const int g = tid & 15, cells_per_pass = blockDim.x >> 4;
+    __syncthreads();
+    for (int d = 0; d < L; ++d) {
+        for (int base = 0; base + d < L; base += cells_per_pass) {
+            const int i = base + (tid >> 4), j = i + d;
+            const bool valid = j < L;
+            int split = kSat;
+            int keep = 0, sweep = 0;
+            if (valid && g == 0) keep = mallb[i * L + j], sweep = mnullb[i * L + j];  // in flight during the loop
+            if (valid) {
+                const int rowi = tri_row(L, i, i) - i;  // + j' = index of (i, j')
+                for (int q = i + 1 + g; q <= j; q += 16)
+                    split = min(split, max(min(kSat, s_wa[q] + s_need[tri_row(L, q, j)]), s_need[rowi + q - 1]));
+            }
+#pragma unroll
+            for (int o = 8; o > 0; o >>= 1) split = min(split, __shfl_xor(split, o));
+            if (valid && g == 0) {
+                int nd = keep;
+                if (d > 0) {
+                    const int opt_all = max(keep, min(kSat, s_wab[i] + s_need[tri_row(L, i + 1, j)]));
+                    nd = min(opt_all, max(sweep, split));
+                }
+                nd = min(nd, kSat);
+                s_need[tri_row(L, i, j)] = nd;
+                need[i * L + j] = nd;
+            }
+        }
+        __syncthreads();
     }
 }
 
@@ -182,53 +247,30 @@ __device__ __forceinline__ uint32_t ld32(rsrc_t tab, uint32_t elem, uint32_t off
     return uint32_t(__builtin_amdgcn_raw_buffer_load_b32(tab, int(off), int(elem << 2), 0));
 }
 
-// Middle splits of every tile of block diagonal D >= 2 (also correct for D = 1).
-// One wave owns an 8x8 sub-tile of cells for 64 consecutive m; lane = m.  For T = 16 the
-// four waves of a work-group cover the 16x16 tile and share operand rows through L1/L2.
+// Middle splits of every tile of block diagonal D >= 2.
+// One wave owns the 8x8 tile of cells for 64 consecutive m; lane = m.  Each loaded operand
+// row is used by 8 cells (1 byte of table traffic per candidate instead of 8).
 // Candidates are compared as float64 keys  cost + (q+1)/256 : one add and one min per
 // candidate give the minimum cost and, among equal costs, the smallest candidate number
 // (all values are integers below 2^34 scaled by 2^-8, exact in float64).
-// Output: cost[] <- unsaturated partial minimum, arg[] <- its candidate number.
-template <int T, int NB, int UNR>
-__global__ void __launch_bounds__(64 * (T / 8) * (T / 8), 2) gemm_kernel(Ctx c, int D) {
-    constexpr bool XCD = false;
-    constexpr int W = T / 8;
-    // NB operand buffers in flight: loads run NB-1 splits ahead
-    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
-    const int rw = wave / W, cw = wave % W;
-    int bx = blockIdx.x, by = blockIdx.y, bz = blockIdx.z;
-    if (XCD) {
-        // Work-groups go round-robin to the 8 XCDs in dispatch order.  Renumber them so that
-        // each XCD works on a contiguous range of (chain, tile, m-chunk).
-        const uint32_t n = gridDim.x * gridDim.y * gridDim.z;
-        const uint32_t id = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-        const uint32_t per = n / 8, main = per * 8;
-        const uint32_t lid = id < main ? (id % 8) * per + id / 8 : id;
-        bx = lid % gridDim.x;
-        by = (lid / gridDim.x) % gridDim.y;
-        bz = lid / (gridDim.x * gridDim.y);
-    }
-    const int b = bz, I = by, J = I + D;
+// Splits whose operands are infeasible for the whole chunk (frontier test) are dropped
+// from the wave's work list before the pipeline starts.
+// Output: cost[] <- unsaturated partial minimum (0xffffffff if none), arg[] <- its number.
+template <int NB, int UNR>
+__global__ void __launch_bounds__(64, 2) gemm_kernel(Ctx c, int D) {
+    constexpr int T = kT;
+    static_assert(T == 8, "one wave per 8x8 tile");
+    const int b = blockIdx.z, I = blockIdx.y, J = I + D;
     const int L = c.L, pitch = c.pitch;
     const int qlo = (I + 1) * T, qhi = J * T;
-
-    // Per-split constants (shift, key offset) go through LDS once: a scalar memory load per
-    // split would put its full latency on the critical path of every pipeline step.
-    __shared__ double s_kq[CKPT_MAX_L + 2];
-    __shared__ int32_t s_sh[CKPT_MAX_L + 2];
-    for (int k = threadIdx.x; k <= qhi - qlo; k += blockDim.x) {
-        s_kq[k] = c.ws.kq[size_t(b) * L + qlo + k];
-        s_sh[k] = c.ws.wsh[size_t(b) * L + qlo + k];
-    }
-    __syncthreads();
-
-    const int j0 = J * T + cw * 8;
-    if (j0 >= L) return;  // ragged last block: this sub-tile has no column
-    const int i0 = I * T + rw * 8;
-    const uint32_t m = bx * 64 + (threadIdx.x & 63);
+    const int j0 = J * T, i0 = I * T;
+    const int lane = threadIdx.x;
+    const uint32_t m = blockIdx.x * 64 + lane;
+    const int m_hi = blockIdx.x * 64 + 63;  // largest m of this wave
     const uint32_t moff = m * 4;
     const size_t chain = size_t(b) * c.rows * pitch;
     const rsrc_t tab = table_rsrc(c.cost + chain, uint32_t(c.rows) * uint32_t(pitch) * 4u);
+    const int32_t* need = c.ws.need + size_t(b) * L * L;
 
     int lrow0[8], jcol[8];
 #pragma unroll
@@ -236,51 +278,92 @@ __global__ void __launch_bounds__(64 * (T / 8) * (T / 8), 2) gemm_kernel(Ctx c, 
 #pragma unroll
     for (int cc = 0; cc < 8; ++cc) jcol[cc] = min(j0 + cc, L - 1);
 
+    // Work list of this wave: the splits q for which some cell of the tile can have both
+    // operands feasible somewhere in this chunk.  Per-split constants (shift, key offset)
+    // travel with the list through LDS, so the pipeline never waits on scalar memory.
+    __shared__ double s_kq[CKPT_MAX_L + 2];
+    __shared__ int32_t s_sh[CKPT_MAX_L + 2];
+    __shared__ int32_t s_q[CKPT_MAX_L + 2];
+    int n = 0;
+    {
+        int out_need = need[(i0 + (lane >> 3)) * L + min(j0 + (lane & 7), L - 1)];
+#pragma unroll
+        for (int o = 32; o > 0; o >>= 1) out_need = min(out_need, __shfl_xor(out_need, o));
+        if (m_hi >= out_need) {
+            for (int base = qlo; base <= qhi; base += 64) {
+                const int q = base + lane;
+                bool active = false;
+                int sh = 0;
+                if (q <= qhi) {
+                    sh = c.ws.wsh[size_t(b) * L + q];
+                    int tl = 1 << 30, tr = 1 << 30;
+#pragma unroll
+                    for (int r = 0; r < 8; ++r) tl = min(tl, need[(i0 + r) * L + q - 1]);
+#pragma unroll
+                    for (int cc = 0; cc < 8; ++cc) tr = min(tr, need[q * L + jcol[cc]]);
+                    active = m_hi >= max(tl, tr + sh);
+                }
+                const unsigned long long mask = __ballot(active);
+                if (active) {
+                    const int pos = n + __popcll(mask & ((1ull << lane) - 1ull));
+                    s_q[pos] = q;
+                    s_sh[pos] = sh;
+                    s_kq[pos] = c.ws.kq[size_t(b) * L + q];
+                }
+                n += __popcll(mask);
+            }
+        }
+        __syncthreads();
+    }
+
     double key[8][8];
 #pragma unroll
     for (int r = 0; r < 8; ++r)
 #pragma unroll
         for (int cc = 0; cc < 8; ++cc) key[r][cc] = 0x1p60;
 
-    uint32_t buf[NB][16];
-    auto load = [&](uint32_t(&v)[16], int q) {
-        const int rq = q * L - (q * (q - 1)) / 2 - q;  // + j = row of (q, j)
-        const int sh = __builtin_amdgcn_readfirstlane(s_sh[q - qlo]);
+    if (n > 0) {
+        uint32_t buf[NB][16];
+        auto load = [&](uint32_t(&v)[16], int k) {
+            const int q = __builtin_amdgcn_readfirstlane(s_q[k]);
+            const int sh = __builtin_amdgcn_readfirstlane(s_sh[k]);
+            const int rq = q * L - (q * (q - 1)) / 2 - q;  // + j = row of (q, j)
 #pragma unroll
-        for (int r = 0; r < 8; ++r) v[r] = ld32(tab, uint32_t(lrow0[r] + q) * uint32_t(pitch), moff);
+            for (int r = 0; r < 8; ++r) v[r] = ld32(tab, uint32_t(lrow0[r] + q) * uint32_t(pitch), moff);
 #pragma unroll
-        for (int cc = 0; cc < 8; ++cc)
-            v[8 + cc] = ld32(tab, uint32_t(rq + jcol[cc]) * uint32_t(pitch) - uint32_t(sh), moff);
-    };
-    auto compute = [&](const uint32_t(&v)[16], int q) {
-        const double cq = s_kq[q - qlo];
-        double lk[8], rk[8];
+            for (int cc = 0; cc < 8; ++cc)
+                v[8 + cc] = ld32(tab, uint32_t(rq + jcol[cc]) * uint32_t(pitch) - uint32_t(sh), moff);
+        };
+        auto compute = [&](const uint32_t(&v)[16], int k) {
+            const double cq = s_kq[k];
+            double lk[8], rk[8];
 #pragma unroll
-        for (int r = 0; r < 8; ++r) lk[r] = double(v[r]);
+            for (int r = 0; r < 8; ++r) lk[r] = double(v[r]);
 #pragma unroll
-        for (int cc = 0; cc < 8; ++cc) rk[cc] = double(v[8 + cc]) + cq;
+            for (int cc = 0; cc < 8; ++cc) rk[cc] = double(v[8 + cc]) + cq;
 #pragma unroll
-        for (int r = 0; r < 8; ++r)
+            for (int r = 0; r < 8; ++r)
 #pragma unroll
-            for (int cc = 0; cc < 8; ++cc) key[r][cc] = fmin(key[r][cc], lk[r] + rk[cc]);
-    };
+                for (int cc = 0; cc < 8; ++cc) key[r][cc] = fmin(key[r][cc], lk[r] + rk[cc]);
+        };
 
-    // Straight-line pipeline: the split list is padded to a multiple of NB by repeating the
-    // last split (a repeated candidate cannot change a minimum), so the loop body has no
-    // branches and the loads of split q + 2 are in flight while split q is evaluated.
+        // Straight-line pipeline: the list is padded to a multiple of the unroll by repeating
+        // its last entry (a repeated candidate cannot change a minimum), so the loop body has
+        // no branches and the loads of entry k + NB - 1 are in flight while entry k is evaluated.
 #pragma unroll
-    for (int u = 0; u < NB - 1; ++u) load(buf[u], min(qlo + u, qhi));
-    constexpr int STEPS = NB * UNR;  // pipeline steps per loop iteration
-    const int iters = (qhi - qlo + STEPS) / STEPS;
-    int q = qlo;
-    for (int it = 0; it < iters; ++it) {
+        for (int u = 0; u < NB - 1; ++u) load(buf[u], min(u, n - 1));
+        constexpr int STEPS = NB * UNR;
+        const int iters = (n + STEPS - 1) / STEPS;
+        int k = 0;
+        for (int it = 0; it < iters; ++it) {
 #pragma unroll
-        for (int u = 0; u < STEPS; ++u) {
-            load(buf[(u + NB - 1) % NB], min(q + NB - 1, qhi));
-            __builtin_amdgcn_sched_barrier(0);  // keep the loads of split q+NB-1 ahead of the math of split q
-            compute(buf[u % NB], min(q, qhi));
-            __builtin_amdgcn_sched_barrier(0);
-            ++q;
+            for (int u = 0; u < STEPS; ++u) {
+                load(buf[(u + NB - 1) % NB], min(k + NB - 1, n - 1));
+                __builtin_amdgcn_sched_barrier(0);  // keep these loads ahead of the math of entry k
+                compute(buf[u % NB], min(k, n - 1));
+                __builtin_amdgcn_sched_barrier(0);
+                ++k;
+            }
         }
     }
 
@@ -292,10 +375,11 @@ __global__ void __launch_bounds__(64 * (T / 8) * (T / 8), 2) gemm_kernel(Ctx c, 
 #pragma unroll
         for (int cc = 0; cc < 8; ++cc) {
             if (j0 + cc < L) {
-                const double k = fmin(key[r][cc], 0x1p33);
-                const double fl = floor(k);
-                c.cost[row + size_t(cc) * pitch] = int32_t(uint32_t(fl) - Pi);
-                c.arg[row + size_t(cc) * pitch] = uint8_t(uint32_t((k - fl) * 256.0));
+                const double k = key[r][cc];
+                const double fl = floor(fmin(k, 0x1p33));
+                const uint32_t cst = k < 0x1p32 ? uint32_t(fl) - Pi : 0xffffffffu;
+                c.cost[row + size_t(cc) * pitch] = int32_t(cst);
+                c.arg[row + size_t(cc) * pitch] = uint8_t(uint32_t((fmin(k, 0x1p33) - fl) * 256.0));
             }
         }
     }
@@ -338,6 +422,27 @@ __global__ void __launch_bounds__(256) row_kernel(Ctx c, int D) {
     int jc[T];
 #pragma unroll
     for (int cc = 0; cc < T; ++cc) jc[cc] = min(jb + cc, L - 1);
+
+    // A wave whose whole chunk lies below the feasibility frontier of every cell of the row
+    // stores "infeasible" and reads nothing.
+    {
+        const int32_t* need = c.ws.need + (size_t(b) * L + i) * L;
+        int row_need = 1 << 30;
+#pragma unroll
+        for (int cc = CF; cc < T; ++cc) row_need = min(row_need, need[jc[cc]]);
+        const int m_hi = __builtin_amdgcn_readfirstlane(int(m)) | 63;
+        if (m_hi < row_need) {
+#pragma unroll
+            for (int cc = CF; cc < T; ++cc) {
+                if (cc < cend) {
+                    const size_t o = chain + size_t(rowi + jc[cc]) * pitch + m;
+                    c.cost[o] = int32_t(kInf);
+                    c.arg[o] = 0;
+                }
+            }
+            return;
+        }
+    }
 
     // ---- every load of this row, issued before anything is consumed ----
     uint32_t nl[NQA], nr[NQA][T];   // near-i: left (i, q-1) and right (q, j) at m - omega_a^q
@@ -422,7 +527,6 @@ template <int T, int DC, int... Rs>
 constexpr std::array<RowFn, sizeof...(Rs)> row_table(std::integer_sequence<int, Rs...>) {
     return {{row_kernel<T, Rs, DC>...}};
 }
-constexpr int kT = 8;  // stage-block size
 const std::array<RowFn, kT> kRow0 = row_table<kT, 0>(std::make_integer_sequence<int, kT>{});
 const std::array<RowFn, kT> kRow1 = row_table<kT, 1>(std::make_integer_sequence<int, kT>{});
 const std::array<RowFn, kT> kRow2 = row_table<kT, 2>(std::make_integer_sequence<int, kT>{});
@@ -470,7 +574,15 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     const int rows = int(ckpt_table_rows(L));
     const Workspace ws = carve(workspace, L, B);
 
-    hipLaunchKernelGGL(precompute_kernel, dim3(B), dim3(64), 0, st, *chains, L, pitch, ws);
+    const size_t frontier_lds = ckpt_table_rows(L) * sizeof(int32_t);
+    if (frontier_lds > 48 * 1024) {
+        // Above the default per-block limit the kernel has to be allowed its LDS size; this sets a
+        // function attribute and allocates nothing.
+        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(precompute_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(frontier_lds))))
+            return CKPT_E_HIP;
+    }
+    hipLaunchKernelGGL(precompute_kernel, dim3(B), dim3(1024), frontier_lds, st, *chains, L, pitch, ws);
     CKPT_AFTER_LAUNCH(CKPT_K_PRECOMPUTE);
     const Ctx ctx{L, M, pitch, rows, ws, cost, arg};
     constexpr int T = kT;
@@ -479,12 +591,7 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     for (int D = 0; D < nblk; ++D) {
         const dim3 tiles_gemm(gx_gemm, nblk - D, B), tiles_row(gx_row, nblk - D, B);
         if (D >= 2) {
-            switch (g_tile.load()) {  // experiment selector
-                case 1: hipLaunchKernelGGL((gemm_kernel<T, 3, 2>), tiles_gemm, dim3(64), 0, st, ctx, D); break;
-                case 2: hipLaunchKernelGGL((gemm_kernel<T, 3, 3>), tiles_gemm, dim3(64), 0, st, ctx, D); break;
-                case 3: hipLaunchKernelGGL((gemm_kernel<T, 2, 4>), tiles_gemm, dim3(64), 0, st, ctx, D); break;
-                default: hipLaunchKernelGGL((gemm_kernel<T, 3, 1>), tiles_gemm, dim3(64), 0, st, ctx, D); break;
-            }
+            hipLaunchKernelGGL((gemm_kernel<3, 3>), tiles_gemm, dim3(64), 0, st, ctx, D);
             CKPT_AFTER_LAUNCH(CKPT_K_GEMM);
         }
         const auto& rowfn = D == 0 ? kRow0 : (D == 1 ? kRow1 : kRow2);
