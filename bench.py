@@ -8,7 +8,7 @@ cells per second, the roofline of the dominant kernel (durations from HIP events
 recorded by the library on the launch stream) and the CPU oracle timed on a bounded
 sample of the same workload.
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu] [--all]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu] [--all] [--calib-copy MIB]
 """
 import argparse
 import json
@@ -19,16 +19,17 @@ import time
 ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
-# Machine peak used for the roofline: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz = 39.3e12
-# 32-bit integer vector operations per second (one per lane per clock; same issue rate as
-# the non-FMA fp32 vector rate, 157.3 TFLOP/s / 4).  HBM3E: 8 TB/s.
-PEAK_INT_OPS = 256 * 64 * 2.4e9
+# Roofs.  HBM3E of one MI355X: 8 TB/s.  Vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz =
+# 39.3e12 lane-operations per second; float64 add/min issue at that rate (78.6 TFLOP/s fp64
+# vector peak counts an FMA as two), and so do 32-bit integer operations.
 PEAK_HBM = 8.0e12
-# Algorithmic work of one min-plus candidate in the dominant kernel (gemm_kernel): one add
-# and one min on a float64 key that carries cost and candidate number together.  float64
-# vector add/min issue at one per lane per clock, the same 39.3e12/s as the integer rate
-# above (= 78.6 TFLOP/s fp64 vector peak / 2, since these are not FMAs).
-OPS_PER_EVAL = 2
+PEAK_VALU_OPS = 256 * 64 * 2.4e9
+# Algorithmic work of gemm_kernel per candidate: 16 operand rows of 4 B feed an 8x8 tile of
+# cells, i.e. 1 byte of table reads per candidate, plus 5 bytes (cost + candidate number) of
+# partial result per cell; one float64 add and one float64 min per candidate.
+GEMM_BYTES_PER_EVAL = 1.0
+GEMM_BYTES_PER_CELL = 5.0
+GEMM_OPS_PER_EVAL = 2
 
 
 def counts(L, M, B):
@@ -37,17 +38,32 @@ def counts(L, M, B):
     return cells, evals
 
 
-def gemm_evals(L, M, B, T):
-    """Candidate evaluations done by gemm_kernel: the splits of a cell that fall strictly
-    between its row block and its column block (plus the first stage of the column block)."""
+def gemm_work(L, M, B, T=8):
+    """(candidates, cells) handled by gemm_kernel per step: for every tile of block diagonal
+    D >= 2 the splits strictly between its row block and its column block, plus the first
+    stage of the column block.  Nominal counts: candidates that the feasibility test drops
+    still count, as infeasible cells do in the headline metric."""
     nblk = (L + T - 1) // T
-    total = 0
+    evals = cells = 0
     for D in range(2, nblk):
         for I in range(nblk - D):
-            J = I + D
-            cols = min(T, L - J * T)
-            total += T * cols * ((D - 1) * T + 1)
-    return total * (M + 1) * B
+            cols = min(T, L - (I + D) * T)
+            cells += T * cols
+            evals += T * cols * ((D - 1) * T + 1)
+    return evals * (M + 1) * B, cells * (M + 1) * B
+
+
+def measured_traffic(workload, kernel):
+    """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary of this
+    workload (profiles/<kernel>_<workload>_pmc.txt, line 'traffic_bytes_per_launch: N'), or None."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return float(line.split(":")[1])
+    except OSError:
+        pass
+    return None
 
 
 def upload(batch, dev):
@@ -127,7 +143,8 @@ def main():
     ap.add_argument("--steps", type=int, default=10)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--config", type=int, default=4, help="workload index 0..4 (default 4: L=192, M=4096, B=8)")
-    ap.add_argument("--tile", type=int, default=0, help="stage-block size of the fill: 8, 16, 0 = library default")
+    ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
+                    help="first copy MIB mebibytes device to device (reference for rocprofv3 --pmc byte counters)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
     ap.add_argument("--all", action="store_true", help="also time the other four workloads (few steps each)")
     a = ap.parse_args()
@@ -141,25 +158,38 @@ def main():
     amd.load_library()
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
-    amd.ckpt_set_tile(a.tile)
+    if a.calib_copy:
+        # a plain device copy of known size, first in the trace: scale for the rocprofv3 byte counters
+        src = torch.empty(a.calib_copy << 20, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     r = run_config(amd, a.config, a.steps, a.warmup, dev)
     batch = r["batch"]
     evals_per_s = r["evals"] / (r["ms"] * 1e-3)
     kinds = r["kinds"]
     dom = "gemm_kernel"
-    dom_evals = gemm_evals(batch.L, batch.M, batch.B, a.tile or 8)
+    dom_evals, dom_cells = gemm_work(batch.L, batch.M, batch.B)
     dom_ms = kinds[dom]["ms_per_step"]
-    ops = OPS_PER_EVAL * dom_evals
-    roofline = {"bound": "alu", "kernel": dom, "achieved": ops / (dom_ms * 1e-3) / 1e12, "peak": PEAK_INT_OPS / 1e12,
-                "unit": "Top/s (fp64 vector add/min, one per lane per clock)", "frac": ops / (dom_ms * 1e-3) / PEAK_INT_OPS, "traffic": None,
-                "launches_per_step": kinds[dom]["launches_per_step"], "kernel_ms_per_step": dom_ms,
-                "ops_per_eval": OPS_PER_EVAL, "evals_in_kernel": dom_evals}
+    launches = max(1, kinds[dom]["launches_per_step"])
+    per_launch_s = dom_ms * 1e-3 / launches
+    alg_bytes = (GEMM_BYTES_PER_EVAL * dom_evals + GEMM_BYTES_PER_CELL * dom_cells) / launches
+    alg_ops = GEMM_OPS_PER_EVAL * dom_evals / launches
+    roofline = {"bound": "hbm", "kernel": dom, "achieved": alg_bytes / per_launch_s / 1e9, "peak": PEAK_HBM / 1e9,
+                "unit": "GB/s", "frac": alg_bytes / per_launch_s / PEAK_HBM,
+                "traffic": measured_traffic(batch.name, dom),
+                "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": per_launch_s * 1e3,
+                "launches_per_step": launches, "evals_in_kernel_per_step": dom_evals,
+                "alu": {"achieved": alg_ops / per_launch_s / 1e12, "peak": PEAK_VALU_OPS / 1e12,
+                        "unit": "Tlane-op/s (float64 add + min per candidate)",
+                        "frac": alg_ops / per_launch_s / PEAK_VALU_OPS}}
     out = {
         "metric": "min-plus candidate evaluations per second (whole batch, tables resident in HBM)",
         "value": evals_per_s, "unit": "evals/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": r["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int32 tables; float64 keys (exact integers) in the dominant kernel", "data": "synthetic",
+        "dtype": "int32", "data": "synthetic",
         "config": {"workload": batch.name, "L": batch.L, "M": batch.M, "B": batch.B, "cells": r["cells"],
                    "evals": r["evals"]},
         "cells_per_s": r["cells"] / (r["ms"] * 1e-3),

@@ -156,13 +156,6 @@ int ckpt_check_inputs(const void* workspace, int L, int M, int B, void* stream, 
 int ckpt_schedule(const uint8_t* arg_host, const int32_t* wa, const int32_t* wabar, int L, int M,
                   int s, int t, int m_budget, ckpt_op_t* ops_out, int ops_cap);
 
-/*
- * Tuning knob: stage-block size of the fill (8 or 16; 0 = let the library choose).
- * Process-wide, affects later ckpt_solve_* calls; results do not depend on it.
- * Returns the previous value, or CKPT_E_ARG.
- */
-int ckpt_set_tile(int T);
-
 /* hipError_t of the most recent failed HIP call made by this library (0 if none). */
 int ckpt_last_hip_error(void);
 /* Static description of a CKPT_* code. */

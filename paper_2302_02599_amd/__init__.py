@@ -6,5 +6,5 @@ paper_2302_02599_amd/build.py).  There is no CPU fallback: loading fails loudly
 when the library is missing.
 """
 from .binding import (CKPT_INF, CkptError, Solution, ckpt_check_inputs, ckpt_row_index,  # noqa: F401
-                      ckpt_row_pitch, ckpt_schedule, ckpt_set_tile, ckpt_solve_batched, ckpt_solve_profiled, ckpt_table_elems,
+                      ckpt_row_pitch, ckpt_schedule, ckpt_solve_batched, ckpt_solve_profiled, ckpt_table_elems,
                       ckpt_table_rows, ckpt_workspace_bytes, lib_path, load_library, solve)

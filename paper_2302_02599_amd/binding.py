@@ -62,7 +62,6 @@ def load_library():
     lib.ckpt_check_inputs.argtypes = [vp, i, i, i, vp, vp]
     lib.ckpt_schedule.restype = i
     lib.ckpt_schedule.argtypes = [vp, vp, vp, i, i, i, i, i, ctypes.POINTER(_Op), i]
-    lib.ckpt_set_tile.restype, lib.ckpt_set_tile.argtypes = i, [i]
     lib.ckpt_last_hip_error.restype, lib.ckpt_last_hip_error.argtypes = i, []
     lib.ckpt_strerror.restype, lib.ckpt_strerror.argtypes = ctypes.c_char_p, [i]
     _lib = lib
@@ -83,14 +82,6 @@ def ckpt_row_index(L: int, s: int, t: int) -> int:
 
 def ckpt_table_elems(L: int, M: int, B: int) -> int:
     return load_library().ckpt_table_elems(L, M, B)
-
-
-def ckpt_set_tile(T: int) -> int:
-    """Stage-block size of the fill (8, 16, or 0 = automatic); returns the previous value."""
-    rc = load_library().ckpt_set_tile(T)
-    if rc < 0:
-        raise CkptError(rc, "ckpt_set_tile")
-    return rc
 
 
 def ckpt_workspace_bytes(L: int, M: int, B: int) -> int:

@@ -531,7 +531,6 @@ const std::array<RowFn, kT> kRow0 = row_table<kT, 0>(std::make_integer_sequence<
 const std::array<RowFn, kT> kRow1 = row_table<kT, 1>(std::make_integer_sequence<int, kT>{});
 const std::array<RowFn, kT> kRow2 = row_table<kT, 2>(std::make_integer_sequence<int, kT>{});
 
-std::atomic<int> g_tile{0};  // 0 = choose automatically
 
 int check_dims(int L, int M, int B) {
     if (L < 1 || M < 0 || B < 1) return CKPT_E_ARG;
@@ -676,10 +675,6 @@ int ckpt_check_inputs(const void* workspace, int L, int M, int B, void* stream, 
 
 int ckpt_last_hip_error(void) { return g_last_hip_error.load(); }
 
-int ckpt_set_tile(int T) {
-    if (T < 0 || T > 16) return CKPT_E_ARG;
-    return g_tile.exchange(T);
-}
 
 const char* ckpt_strerror(int code) {
     switch (code) {

@@ -13,17 +13,13 @@ pytestmark = pytest.mark.gpu
 _full = {}
 
 
-@pytest.fixture(scope="module", params=[0], ids=["default"])
-def amd(request):
-    """The library, once per stage-block size of the fill (results must not depend on it)."""
+@pytest.fixture(scope="module")
+def amd():
     import torch
     assert torch.cuda.is_available(), "GPU tests need a GPU"
     import paper_2302_02599_amd as amd
     amd.load_library()          # raises if the HIP library is not built: there is no fallback
-    _full.clear()
-    amd.ckpt_set_tile(request.param)
-    yield amd
-    amd.ckpt_set_tile(0)
+    return amd
 
 
 @pytest.mark.parametrize("cfg", [0, 1, 2])
