@@ -18,6 +18,7 @@ namespace {
 
 constexpr uint32_t kInf = 1u << 30;
 constexpr int kT = 8;  // stage-block size of the fill
+constexpr int kCH = 4;  // 64-column chunks of m per gemm work-group
 std::atomic<int> g_last_hip_error{0};
 
 inline bool hip_ok(hipError_t e) {
@@ -256,17 +257,19 @@ __device__ __forceinline__ uint32_t ld32(rsrc_t tab, uint32_t elem, uint32_t off
 // Splits whose operands are infeasible for the whole chunk (frontier test) are dropped
 // from the wave's work list before the pipeline starts.
 // Output: cost[] <- unsaturated partial minimum (0xffffffff if none), arg[] <- its number.
-template <int NB, int UNR>
-__global__ void __launch_bounds__(64, 2) gemm_kernel(Ctx c, int D) {
+template <int NB, int UNR, int CH>
+__global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
     constexpr int T = kT;
     static_assert(T == 8, "one wave per 8x8 tile");
     const int b = blockIdx.z, I = blockIdx.y, J = I + D;
     const int L = c.L, pitch = c.pitch;
     const int qlo = (I + 1) * T, qhi = J * T;
     const int j0 = J * T, i0 = I * T;
-    const int lane = threadIdx.x;
-    const uint32_t m = blockIdx.x * 64 + lane;
-    const int m_hi = blockIdx.x * 64 + 63;  // largest m of this wave
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
+    const int chunk = blockIdx.x * CH + wave;  // this wave's 64 columns of m
+    const uint32_t m = chunk * 64 + lane;
+    const int m_hi = min(int(blockIdx.x * CH + CH) * 64, pitch) - 1;  // largest m of the work-group
     const uint32_t moff = m * 4;
     const size_t chain = size_t(b) * c.rows * pitch;
     const rsrc_t tab = table_rsrc(c.cost + chain, uint32_t(c.rows) * uint32_t(pitch) * 4u);
@@ -284,8 +287,9 @@ __global__ void __launch_bounds__(64, 2) gemm_kernel(Ctx c, int D) {
     __shared__ double s_kq[CKPT_MAX_L + 2];
     __shared__ int32_t s_sh[CKPT_MAX_L + 2];
     __shared__ int32_t s_q[CKPT_MAX_L + 2];
-    int n = 0;
-    {
+    __shared__ int32_t s_n;
+    if (wave == 0) {
+        int n = 0;
         int out_need = need[(i0 + (lane >> 3)) * L + min(j0 + (lane & 7), L - 1)];
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) out_need = min(out_need, __shfl_xor(out_need, o));
@@ -313,8 +317,11 @@ __global__ void __launch_bounds__(64, 2) gemm_kernel(Ctx c, int D) {
                 n += __popcll(mask);
             }
         }
-        __syncthreads();
+        if (lane == 0) s_n = n;
     }
+    __syncthreads();
+    const int n = s_n;
+    if (chunk * 64 >= pitch) return;
 
     double key[8][8];
 #pragma unroll
@@ -590,7 +597,7 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     for (int D = 0; D < nblk; ++D) {
         const dim3 tiles_gemm(gx_gemm, nblk - D, B), tiles_row(gx_row, nblk - D, B);
         if (D >= 2) {
-            hipLaunchKernelGGL((gemm_kernel<3, 3>), tiles_gemm, dim3(64), 0, st, ctx, D);
+            hipLaunchKernelGGL((gemm_kernel<3, 3, kCH>), dim3((gx_gemm + kCH - 1) / kCH, nblk - D, B), dim3(64 * kCH), 0, st, ctx, D);
             CKPT_AFTER_LAUNCH(CKPT_K_GEMM);
         }
         const auto& rowfn = D == 0 ? kRow0 : (D == 1 ? kRow1 : kRow2);
