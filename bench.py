@@ -114,6 +114,43 @@ def run_config(amd, idx, steps, warmup, dev, profile=True):
     return dict(batch=batch, ms=wall / steps * 1e3, cells=cells, evals=evals, kinds=kinds)
 
 
+def time_planner_steps(amd, idx, dev, reps=20):
+    """Microseconds per call of the planner-side steps on workload idx (tables already filled)."""
+    import numpy as np
+    import torch
+    from workloads import make_config
+    batch = make_config(idx)
+    L, M, B = batch.L, batch.M, batch.B
+    sol = amd.solve(batch, device=str(dev))
+    wa, wabar = torch.from_numpy(batch.wa).to(dev), torch.from_numpy(batch.wabar).to(dev)
+    budgets = torch.full((B,), M, dtype=torch.int32, device=dev)
+    out = torch.zeros(2, dtype=torch.int32, device=dev)
+    cap = L * (L + 1) // 2 + L
+    ops = torch.zeros((B, cap, 2), dtype=torch.uint8, device=dev)
+    n_ops = torch.zeros(B, dtype=torch.int32, device=dev)
+    ws = torch.empty(amd.ckpt_schedule_workspace_bytes(L, B), dtype=torch.uint8, device=dev)
+    by_wa, by_wabar = wa.to(torch.int64) * 1000, wabar.to(torch.int64) * 1000
+    budget_bytes = torch.full((B,), 1000 * M, dtype=torch.int64, device=dev)
+    o_wa, o_wabar = torch.empty_like(wa), torch.empty_like(wabar)
+    steps = {
+        "ckpt_select_plan": lambda: amd.ckpt_select_plan(sol.cost, L, M, B, budgets, out),
+        "ckpt_schedule_batched": lambda: amd.ckpt_schedule_batched(sol.arg, wa, wabar, L, M, B, budgets, ops, cap,
+                                                                   n_ops, ws),
+        "ckpt_discretize": lambda: amd.ckpt_discretize(by_wa, by_wabar, budget_bytes, L, M, B, o_wa, o_wabar),
+    }
+    res = {}
+    for name, fn in steps.items():
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        res[name] = (time.perf_counter() - t0) / reps * 1e6
+    assert (o_wa == wa).all() and int(out[0]) >= 0 and int(n_ops.min()) > 0
+    return {"workload": batch.name, "us_per_call": res}
+
+
 def cpu_baseline(idx, budget_s=25.0):
     """The oracle as it stands, on the host cores, on a bounded sample of the workload:
     whole chains of the batch, one after the other, until about budget_s seconds are spent."""
@@ -205,6 +242,7 @@ def main():
             others[o["batch"].name] = {"ms_per_step": o["ms"], "evals_per_s": o["evals"] / (o["ms"] * 1e-3),
                                        "cells_per_s": o["cells"] / (o["ms"] * 1e-3)}
         out["other_workloads"] = others
+        out["planner_steps"] = time_planner_steps(amd, a.config, dev)
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(a.config)
     else:

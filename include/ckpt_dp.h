@@ -156,6 +156,55 @@ int ckpt_check_inputs(const void* workspace, int L, int M, int B, void* stream, 
 int ckpt_schedule(const uint8_t* arg_host, const int32_t* wa, const int32_t* wabar, int L, int M,
                   int s, int t, int m_budget, ckpt_op_t* ops_out, int ops_cap);
 
+/*
+ * Planner-side steps around the table fill (Section "Integrate Two Solvers": the planner
+ * solves one chain per candidate intra-op plan and keeps the plan with the shortest total
+ * time).  All three only enqueue work on `stream` and allocate nothing.
+ */
+
+/*
+ * Plan selection: out[0] = the chain b with the smallest C_BP(1, L, m_b), the smallest b
+ * on ties, -1 if no chain is feasible; out[1] = that cost (CKPT_INF if none).
+ *   cost      DEVICE cost table filled by ckpt_solve_batched
+ *   m_budget  DEVICE int32 [B]: memory for the whole chain of plan b, input a^0 already
+ *             subtracted; values above M read column M, negative values are infeasible
+ *   out       DEVICE int32 [2]
+ * Returns CKPT_OK, CKPT_E_ARG, CKPT_E_LIMIT or CKPT_E_HIP.
+ */
+int ckpt_select_plan(const int32_t* cost, int L, int M, int B, const int32_t* m_budget, void* stream,
+                     int32_t* out);
+
+/*
+ * Memory discretisation (the step the paper inherits from Rotor without describing it):
+ * the byte budget of chain b is cut into M equal slots and every size is rounded up,
+ *     slots = min(2^31 - 1, ceil(bytes * M / budget_bytes[b])),   exact integer arithmetic.
+ *   bytes_*      DEVICE int64, shapes as the int32 arrays of ckpt_chains_t; bytes_wdelta,
+ *                bytes_of, bytes_ob may be NULL (then the matching output is not written)
+ *   budget_bytes DEVICE int64 [B], each > 0
+ *   out          host struct of DEVICE int32 output pointers (uf, ub are ignored)
+ * Preconditions (not checked): 0 <= bytes < 2^42, M <= 2^20, budget > 0.
+ * Returns CKPT_OK, CKPT_E_ARG, CKPT_E_LIMIT or CKPT_E_HIP.
+ */
+int ckpt_discretize(const int64_t* bytes_wa, const int64_t* bytes_wabar, const int64_t* bytes_wdelta,
+                    const int64_t* bytes_of, const int64_t* bytes_ob, const int64_t* budget_bytes, int L,
+                    int M, int B, void* stream, const ckpt_chains_t* out);
+
+/*
+ * ckpt_schedule for every chain at once, on the device: chain b is walked from cell
+ * (1, L, min(m_budget[b], M)).
+ *   arg        DEVICE arg table; wa, wabar DEVICE arrays of ckpt_chains_t shape
+ *   ops        DEVICE [B][ops_cap]; ops_cap >= L(L+1)/2 + L always suffices
+ *   n_ops      DEVICE int32 [B]: number of operations of chain b, or CKPT_E_INFEASIBLE,
+ *              CKPT_E_SMALLBUF, CKPT_E_CORRUPT, CKPT_E_ARG (negative budget) for that chain
+ *   workspace  DEVICE memory of ckpt_schedule_workspace_bytes(L, B) bytes
+ * Returns CKPT_OK, CKPT_E_ARG, CKPT_E_LIMIT or CKPT_E_HIP.
+ */
+int ckpt_schedule_batched(const uint8_t* arg, const int32_t* wa, const int32_t* wabar, int L, int M, int B,
+                          const int32_t* m_budget, void* stream, ckpt_op_t* ops, int ops_cap, int32_t* n_ops,
+                          void* workspace);
+/* Bytes of DEVICE workspace (16-byte aligned) ckpt_schedule_batched needs: the walk stacks. */
+size_t ckpt_schedule_workspace_bytes(int L, int B);
+
 /* hipError_t of the most recent failed HIP call made by this library (0 if none). */
 int ckpt_last_hip_error(void);
 /* Static description of a CKPT_* code. */

@@ -159,3 +159,42 @@ def infeasible_fraction(L, M, wa, wabar, wdelta=None, of=None, ob=None):
     need = min_feasible_memory(L, wa, wabar, wdelta, of, ob)
     iu = np.triu_indices(L)
     return float(np.minimum(need[iu], M + 1).sum()) / (len(iu[0]) * (M + 1))
+
+
+def select_plan(costs, L, m_budget):
+    """Final step of the planner's loop over candidate intra-op plans (Section "Integrate Two
+    Solvers"): among the chains b, the one with the shortest total time C_BP(1, L, m_b) at its
+    own budget m_b; the smallest b on ties; (-1, INF) if no chain is feasible.  A budget above
+    the table's M reads column M; a negative budget is infeasible.
+
+    costs: list of per-chain tables as returned by solve_chain; m_budget: list of ints.
+    """
+    best_b, best = -1, INF
+    for b, (table, m) in enumerate(zip(costs, m_budget)):
+        if m < 0:
+            continue
+        M = table.shape[2] - 1
+        value = int(table[0, L - 1, min(int(m), M)])
+        if value < best:
+            best_b, best = b, value
+    return best_b, best
+
+
+SLOT_MAX = (1 << 31) - 1
+
+
+def discretize(sizes_bytes, budget_bytes, M):
+    """Memory discretisation the paper inherits from Rotor without describing it: the device
+    budget is cut into M equal slots and every size is rounded UP to whole slots, so that a
+    schedule that fits in slots fits in bytes:  slots = ceil(size * M / budget), computed in
+    exact integer arithmetic and clamped to 2^31 - 1.  Python ints, no overflow."""
+    budget = int(budget_bytes)
+    if budget <= 0 or M < 0:
+        raise ValueError("budget must be positive")
+    out = []
+    for v in sizes_bytes:
+        v = int(v)
+        if v < 0:
+            raise ValueError("negative size")
+        out.append(min(SLOT_MAX, -((-v * M) // budget)))
+    return out

@@ -62,6 +62,13 @@ def load_library():
     lib.ckpt_check_inputs.argtypes = [vp, i, i, i, vp, vp]
     lib.ckpt_schedule.restype = i
     lib.ckpt_schedule.argtypes = [vp, vp, vp, i, i, i, i, i, ctypes.POINTER(_Op), i]
+    lib.ckpt_select_plan.restype = i
+    lib.ckpt_select_plan.argtypes = [vp, i, i, i, vp, vp, vp]
+    lib.ckpt_discretize.restype = i
+    lib.ckpt_discretize.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp, ctypes.POINTER(_Chains)]
+    lib.ckpt_schedule_batched.restype = i
+    lib.ckpt_schedule_batched.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp, i, vp, vp]
+    lib.ckpt_schedule_workspace_bytes.restype, lib.ckpt_schedule_workspace_bytes.argtypes = sz, [i, i]
     lib.ckpt_last_hip_error.restype, lib.ckpt_last_hip_error.argtypes = i, []
     lib.ckpt_strerror.restype, lib.ckpt_strerror.argtypes = ctypes.c_char_p, [i]
     _lib = lib
@@ -172,6 +179,63 @@ def ckpt_schedule(arg_host: np.ndarray, wa: np.ndarray, wabar: np.ndarray, L: in
     if rc < 0:
         raise CkptError(rc, "ckpt_schedule")
     return [(ops[i].kind, ops[i].stage) for i in range(rc)]
+
+
+def _stream(stream):
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream if stream is None else stream)
+
+
+def _dev(t, name, dtype, numel):
+    import torch
+    if t is None:
+        return None
+    if not (isinstance(t, torch.Tensor) and t.is_cuda and t.dtype == dtype and t.is_contiguous() and t.numel() >= numel):
+        raise TypeError(f"{name}: expected a contiguous {dtype} device tensor of at least {numel} elements")
+    return t.data_ptr()
+
+
+def ckpt_select_plan(cost, L, M, B, m_budget, out, *, stream=None) -> None:
+    """out[0] <- best chain (or -1), out[1] <- its cost.  All tensors on the device."""
+    import torch
+    rc = load_library().ckpt_select_plan(_dev(cost, "cost", torch.int32, ckpt_table_elems(L, M, B)), L, M, B,
+                                         _dev(m_budget, "m_budget", torch.int32, B), _stream(stream),
+                                         _dev(out, "out", torch.int32, 2))
+    if rc != 0:
+        raise CkptError(rc, "ckpt_select_plan")
+
+
+def ckpt_discretize(bytes_wa, bytes_wabar, budget_bytes, L, M, B, wa, wabar, *, bytes_wdelta=None, bytes_of=None,
+                    bytes_ob=None, wdelta=None, of=None, ob=None, stream=None) -> None:
+    """int64 byte sizes [B, ...] -> int32 slot sizes, slots = ceil(bytes * M / budget_bytes[b])."""
+    import torch
+    i64, i32 = torch.int64, torch.int32
+    outs = _Chains(None, None, _dev(wa, "wa", i32, B * (L + 1)), _dev(wabar, "wabar", i32, B * L),
+                   _dev(wdelta, "wdelta", i32, B * (L + 1)), _dev(of, "of", i32, B * L), _dev(ob, "ob", i32, B * L))
+    rc = load_library().ckpt_discretize(_dev(bytes_wa, "bytes_wa", i64, B * (L + 1)),
+                                        _dev(bytes_wabar, "bytes_wabar", i64, B * L),
+                                        _dev(bytes_wdelta, "bytes_wdelta", i64, B * (L + 1)),
+                                        _dev(bytes_of, "bytes_of", i64, B * L), _dev(bytes_ob, "bytes_ob", i64, B * L),
+                                        _dev(budget_bytes, "budget_bytes", i64, B), L, M, B, _stream(stream),
+                                        ctypes.byref(outs))
+    if rc != 0:
+        raise CkptError(rc, "ckpt_discretize")
+
+
+def ckpt_schedule_workspace_bytes(L: int, B: int) -> int:
+    return load_library().ckpt_schedule_workspace_bytes(L, B)
+
+
+def ckpt_schedule_batched(arg, wa, wabar, L, M, B, m_budget, ops, ops_cap, n_ops, workspace, *, stream=None) -> None:
+    """Device walk of every chain: ops uint8 [B, ops_cap, 2] (kind, stage), n_ops int32 [B]."""
+    import torch
+    rc = load_library().ckpt_schedule_batched(
+        _dev(arg, "arg", torch.uint8, ckpt_table_elems(L, M, B)), _dev(wa, "wa", torch.int32, B * (L + 1)),
+        _dev(wabar, "wabar", torch.int32, B * L), L, M, B, _dev(m_budget, "m_budget", torch.int32, B), _stream(stream),
+        _dev(ops, "ops", torch.uint8, B * ops_cap * 2), ops_cap, _dev(n_ops, "n_ops", torch.int32, B),
+        _dev(workspace, "workspace", torch.uint8, ckpt_schedule_workspace_bytes(L, B)))
+    if rc != 0:
+        raise CkptError(rc, "ckpt_schedule_batched")
 
 
 @dataclass

@@ -539,6 +539,99 @@ const std::array<RowFn, kT> kRow1 = row_table<kT, 1>(std::make_integer_sequence<
 const std::array<RowFn, kT> kRow2 = row_table<kT, 2>(std::make_integer_sequence<int, kT>{});
 
 
+// ---------------------------------------------------------------------------
+// Planner-side steps (Section "Integrate Two Solvers").
+// ---------------------------------------------------------------------------
+
+// One block: lexicographic minimum of (C_BP(1, L, m_b), b) over the chains.
+__global__ void __launch_bounds__(256) select_kernel(const int32_t* __restrict__ cost, int L, int M, int pitch,
+                                                      int rows, int B, const int32_t* __restrict__ m_budget,
+                                                      int32_t* __restrict__ out) {
+    __shared__ unsigned long long s_best[256];
+    const size_t root = size_t(tri_row(L, 0, L - 1)) * pitch;
+    unsigned long long best = (static_cast<unsigned long long>(kInf) << 32) | 0xffffffffull;
+    for (int b = threadIdx.x; b < B; b += blockDim.x) {
+        const int m = m_budget[b];
+        if (m < 0) continue;
+        const uint32_t v = uint32_t(cost[size_t(b) * rows * pitch + root + min(m, M)]);
+        if (v < kInf) best = min(best, (static_cast<unsigned long long>(v) << 32) | uint32_t(b));
+    }
+    s_best[threadIdx.x] = best;
+    __syncthreads();
+    for (int o = blockDim.x / 2; o > 0; o >>= 1) {
+        if (int(threadIdx.x) < o) s_best[threadIdx.x] = min(s_best[threadIdx.x], s_best[threadIdx.x + o]);
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const unsigned long long r = s_best[0];
+        out[0] = (r >> 32) < kInf ? int32_t(r & 0xffffffffull) : -1;
+        out[1] = int32_t(r >> 32);
+    }
+}
+
+// slots = min(2^31 - 1, ceil(bytes * M / budget)); one thread per element, one chain per blockIdx.y.
+__global__ void __launch_bounds__(256) discretize_kernel(const long long* __restrict__ in, int32_t* __restrict__ out,
+                                                          const long long* __restrict__ budget, int per_chain, int M) {
+    const int b = blockIdx.y;
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= per_chain) return;
+    const unsigned long long bud = static_cast<unsigned long long>(budget[b]);
+    const unsigned long long v = static_cast<unsigned long long>(in[size_t(b) * per_chain + k]) * uint32_t(M);
+    const unsigned long long q = bud ? v / bud + (v % bud != 0) : 0x7fffffffull;
+    out[size_t(b) * per_chain + k] = int32_t(min(q, 0x7fffffffull));
+}
+
+// One thread per chain walks its recorded candidates with an explicit stack.  Pending work
+// is either "walk cell (s, t, m)" or "emit B^s"; at most 2 entries per open segment.
+__global__ void __launch_bounds__(64) schedule_kernel(const uint8_t* __restrict__ arg, const int32_t* __restrict__ wa,
+                                                       const int32_t* __restrict__ wabar, int L, int M, int pitch,
+                                                       int rows, int B, const int32_t* __restrict__ m_budget,
+                                                       ckpt_op_t* __restrict__ ops, int cap, int32_t* __restrict__ n_ops,
+                                                       int4* __restrict__ stack_mem) {
+    const int b = blockIdx.x * blockDim.x + threadIdx.x;
+    if (b >= B) return;
+    const uint8_t* tab = arg + size_t(b) * rows * pitch;
+    const int32_t* a = wa + size_t(b) * (L + 1);
+    const int32_t* ab = wabar + size_t(b) * L;
+    ckpt_op_t* out = ops + size_t(b) * cap;
+    int4* stack = stack_mem + size_t(b) * (2 * L + 2);  // (s, t, m, kind): kind 0 walk, 1 emit B^s
+    int top = 0, n = 0, err = 0;
+    auto emit = [&](int kind, int stage) {
+        if (n >= cap) { err = CKPT_E_SMALLBUF; return; }
+        out[n].kind = uint8_t(kind);
+        out[n].stage = uint8_t(stage);
+        ++n;
+    };
+    const int m0 = m_budget[b];
+    if (m0 < 0) err = CKPT_E_ARG;
+    stack[top++] = make_int4(1, L, min(m0, M), 0);
+    bool root = true;
+    while (top > 0 && err == 0) {
+        const int4 e = stack[--top];
+        const int s = e.x, t = e.y, m = e.z;
+        if (e.w == 1) { emit(CKPT_OP_B, s); continue; }
+        if (m < 0) { err = CKPT_E_CORRUPT; break; }
+        const int k = tab[size_t(tri_row(L, s - 1, t - 1)) * pitch + m];
+        if (k == 0) { err = root ? CKPT_E_INFEASIBLE : CKPT_E_CORRUPT; break; }
+        root = false;
+        if (k < s || k > t) { err = CKPT_E_CORRUPT; break; }
+        if (s == t) {
+            emit(CKPT_OP_F_ALL, s);
+            emit(CKPT_OP_B, s);
+        } else if (k == s) {  // C_all: F_all^s, (s+1, t, m - abar^s), B^s
+            emit(CKPT_OP_F_ALL, s);
+            stack[top++] = make_int4(s, s, 0, 1);
+            stack[top++] = make_int4(s + 1, t, m - ab[s - 1], 0);
+        } else {  // C_ck at s' = k: F_ck^s, F_null^{s+1..k-1}, (k, t, m - a^{k-1}), (s, k-1, m)
+            emit(CKPT_OP_F_CK, s);
+            for (int j = s + 1; j < k; ++j) emit(CKPT_OP_F_NULL, j);
+            stack[top++] = make_int4(s, k - 1, m, 0);
+            stack[top++] = make_int4(k, t, m - a[k - 1], 0);
+        }
+    }
+    n_ops[b] = err ? err : n;
+}
+
 int check_dims(int L, int M, int B) {
     if (L < 1 || M < 0 || B < 1) return CKPT_E_ARG;
     if (L > CKPT_MAX_L) return CKPT_E_LIMIT;
@@ -678,6 +771,53 @@ int ckpt_check_inputs(const void* workspace, int L, int M, int B, void* stream, 
     for (int b = 0; b < B; ++b)
         if (flags_host[b]) return CKPT_E_INPUT;
     return CKPT_OK;
+}
+
+int ckpt_select_plan(const int32_t* cost, int L, int M, int B, const int32_t* m_budget, void* stream,
+                     int32_t* out) {
+    if (!cost || !m_budget || !out) return CKPT_E_ARG;
+    if (int rc = check_dims(L, M, B)) return rc;
+    hipLaunchKernelGGL(select_kernel, dim3(1), dim3(256), 0, static_cast<hipStream_t>(stream), cost, L, M,
+                       int(ckpt_row_pitch(M)), int(ckpt_table_rows(L)), B, m_budget, out);
+    return hip_ok(hipGetLastError()) ? CKPT_OK : CKPT_E_HIP;
+}
+
+int ckpt_discretize(const int64_t* bytes_wa, const int64_t* bytes_wabar, const int64_t* bytes_wdelta,
+                    const int64_t* bytes_of, const int64_t* bytes_ob, const int64_t* budget_bytes, int L,
+                    int M, int B, void* stream, const ckpt_chains_t* out) {
+    if (!bytes_wa || !bytes_wabar || !budget_bytes || !out || !out->wa || !out->wabar) return CKPT_E_ARG;
+    if ((bytes_wdelta && !out->wdelta) || (bytes_of && !out->of) || (bytes_ob && !out->ob)) return CKPT_E_ARG;
+    if (int rc = check_dims(L, M, B)) return rc;
+    if (M > (1 << 20)) return CKPT_E_LIMIT;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    struct Job { const int64_t* in; const int32_t* out; int n; };
+    const Job jobs[5] = {{bytes_wa, out->wa, L + 1}, {bytes_wabar, out->wabar, L}, {bytes_wdelta, out->wdelta, L + 1},
+                         {bytes_of, out->of, L}, {bytes_ob, out->ob, L}};
+    for (const Job& j : jobs) {
+        if (!j.in) continue;
+        hipLaunchKernelGGL(discretize_kernel, dim3((j.n + 255) / 256, B), dim3(256), 0, st,
+                           reinterpret_cast<const long long*>(j.in), const_cast<int32_t*>(j.out),
+                           reinterpret_cast<const long long*>(budget_bytes), j.n, M);
+        if (!hip_ok(hipGetLastError())) return CKPT_E_HIP;
+    }
+    return CKPT_OK;
+}
+
+size_t ckpt_schedule_workspace_bytes(int L, int B) {
+    if (L < 1 || B < 1) return 0;
+    return size_t(B) * (2 * size_t(L) + 2) * sizeof(int4);
+}
+
+int ckpt_schedule_batched(const uint8_t* arg, const int32_t* wa, const int32_t* wabar, int L, int M, int B,
+                          const int32_t* m_budget, void* stream, ckpt_op_t* ops, int ops_cap, int32_t* n_ops,
+                          void* workspace) {
+    if (!arg || !wa || !wabar || !m_budget || !ops || !n_ops || !workspace || ops_cap < 0) return CKPT_E_ARG;
+    if (reinterpret_cast<uintptr_t>(workspace) & 15) return CKPT_E_ARG;
+    if (int rc = check_dims(L, M, B)) return rc;
+    hipLaunchKernelGGL(schedule_kernel, dim3((B + 63) / 64), dim3(64), 0, static_cast<hipStream_t>(stream), arg, wa,
+                       wabar, L, M, int(ckpt_row_pitch(M)), int(ckpt_table_rows(L)), B, m_budget, ops, ops_cap,
+                       n_ops, static_cast<int4*>(workspace));
+    return hip_ok(hipGetLastError()) ? CKPT_OK : CKPT_E_HIP;
 }
 
 int ckpt_last_hip_error(void) { return g_last_hip_error.load(); }

@@ -132,3 +132,23 @@ def test_schedule_worst_case_length_fits_default_capacity(amd):
             tab[amd.ckpt_row_index(L, s, t), :] = t
     ops = amd.ckpt_schedule(tab, np.zeros(L + 1, np.int32), np.zeros(L, np.int32), L, M, 1, L, M)
     assert len(ops) == L * (L + 1) // 2 + L
+
+
+def test_planner_steps_reject_bad_arguments_before_touching_the_gpu(amd):
+    lib = amd.load_library()
+    from paper_2302_02599_amd.binding import _Chains
+    assert lib.ckpt_select_plan(None, 4, 8, 1, 256, None, 256) == -1
+    assert lib.ckpt_select_plan(256, 4, 8, 1, 256, None, None) == -1
+    assert lib.ckpt_select_plan(256, 0, 8, 1, 256, None, 256) == -1
+    assert lib.ckpt_select_plan(256, 255, 8, 1, 256, None, 256) == -2
+    outs = _Chains(None, None, 256, 256, None, None, None)
+    f = lib.ckpt_discretize
+    assert f(256, 256, None, None, None, 256, 4, 8, 1, None, None) == -1
+    assert f(None, 256, None, None, None, 256, 4, 8, 1, None, ctypes.byref(outs)) == -1
+    assert f(256, 256, 256, None, None, 256, 4, 8, 1, None, ctypes.byref(outs)) == -1   # input without its output
+    assert f(256, 256, None, None, None, 256, 4, (1 << 20) + 1, 1, None, ctypes.byref(outs)) == -2
+    g = lib.ckpt_schedule_batched
+    assert g(256, 256, 256, 4, 8, 1, 256, None, 256, 10, 256, None) == -1               # no workspace
+    assert g(256, 256, 256, 4, 8, 1, 256, None, 256, 10, 256, 264) == -1                # misaligned workspace
+    assert g(256, 256, 256, 4, 8, 1, 256, None, 256, -1, 256, 256) == -1
+    assert amd.ckpt_schedule_workspace_bytes(8, 3) == 3 * 18 * 16 and amd.ckpt_schedule_workspace_bytes(0, 3) == 0

@@ -1,0 +1,152 @@
+"""GPU parity of the planner-side steps: plan selection, discretisation, batched schedule walk.
+Integer work: exact equality with the oracle."""
+import numpy as np
+import pytest
+
+from workloads import ChainBatch, make_config
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def amd():
+    import torch
+    assert torch.cuda.is_available()
+    import paper_2302_02599_amd as amd
+    amd.load_library()
+    return amd
+
+
+@pytest.fixture(scope="module")
+def solved(amd, oracle_mod):
+    batch = make_config(2)
+    sol = amd.solve(batch)
+    tables = oracle_mod.solve_batch(batch, nthreads=8)
+    return batch, sol, tables
+
+
+def _budget_sets(batch, tables, oracle_mod):
+    L, M, B = batch.L, batch.M, batch.B
+    rng = np.random.default_rng(5)
+    first = [int(np.argmax(t[0][0, L - 1] < oracle_mod.INF)) for t in tables]
+    yield "full", [M] * B
+    yield "random", rng.integers(0, M, B, endpoint=True).tolist()
+    yield "none_feasible", [f - 1 for f in first]
+    yield "one_feasible", [f - 1 for f in first[:-1]] + [first[-1]]
+    yield "mixed_signs_and_overshoot", [(-1 if b % 3 == 0 else M + 50 * b) for b in range(B)]
+
+
+def test_select_plan(amd, oracle_mod, solved):
+    import torch
+    batch, sol, tables = solved
+    L, M, B = batch.L, batch.M, batch.B
+    for name, budgets in _budget_sets(batch, tables, oracle_mod):
+        out = torch.full((2,), -7, dtype=torch.int32, device="cuda")
+        amd.ckpt_select_plan(sol.cost, L, M, B, torch.tensor(budgets, dtype=torch.int32, device="cuda"), out)
+        want = oracle_mod.select_plan([t[0] for t in tables], L, budgets)
+        assert tuple(out.cpu().tolist()) == want, name
+
+
+def test_select_plan_many_chains_and_ties(amd, oracle_mod):
+    """More chains than threads of the selection block, with duplicated chains (ties)."""
+    import torch
+    base = make_config(1)
+    B = 600
+    reps = lambda a: np.repeat(a, B, axis=0)
+    batch = ChainBatch("ties", base.L, 160, B, reps(base.uf), reps(base.ub), reps(base.wa), reps(base.wabar))
+    batch.uf = batch.uf.copy()
+    batch.uf[:300, 0] += 3           # the first half is slower: the winner is chain 300, not 0
+    sol = amd.solve(batch)
+    budgets = [160] * B
+    out = torch.zeros(2, dtype=torch.int32, device="cuda")
+    amd.ckpt_select_plan(sol.cost, batch.L, batch.M, B, torch.tensor(budgets, dtype=torch.int32, device="cuda"), out)
+    t_slow = oracle_mod.solve_chain(batch.L, batch.M, *batch.chain(0))[0]
+    t_fast = oracle_mod.solve_chain(batch.L, batch.M, *batch.chain(300))[0]
+    want = oracle_mod.select_plan([t_slow] * 300 + [t_fast] * 300, batch.L, budgets)
+    assert want[0] == 300 and tuple(out.cpu().tolist()) == want
+
+
+@pytest.mark.parametrize("L,M,B,seed", [(1, 1, 1, 0), (7, 64, 3, 1), (48, 1024, 16, 2), (192, 4096, 8, 3), (33, 1 << 20, 2, 4)])
+def test_discretize(amd, oracle_mod, L, M, B, seed):
+    import torch
+    rng = np.random.default_rng(seed)
+    big = 1 << 41
+    arrays = {"wa": rng.integers(0, big, (B, L + 1)), "wabar": rng.integers(0, big, (B, L)),
+              "wdelta": rng.integers(0, 1 << 20, (B, L + 1)), "of": rng.integers(0, 3, (B, L)),
+              "ob": rng.integers(0, big, (B, L))}
+    budget = rng.integers(1, 1 << 40, B)
+    if B > 1:
+        budget[-1] = 1                                 # huge quotients: clamps
+    arrays["wa"][0, 0] = 0
+    arrays["wabar"][0, 0] = int(budget[0])            # exactly the whole budget -> M slots
+    dev = {k: torch.from_numpy(v.astype(np.int64)).cuda() for k, v in arrays.items()}
+    outs = {k: torch.full(v.shape, -1, dtype=torch.int32, device="cuda") for k, v in arrays.items()}
+    amd.ckpt_discretize(dev["wa"], dev["wabar"], torch.from_numpy(budget.astype(np.int64)).cuda(), L, M, B,
+                        outs["wa"], outs["wabar"], bytes_wdelta=dev["wdelta"], bytes_of=dev["of"], bytes_ob=dev["ob"],
+                        wdelta=outs["wdelta"], of=outs["of"], ob=outs["ob"])
+    for k, v in arrays.items():
+        got = outs[k].cpu().numpy()
+        for b in range(B):
+            assert got[b].tolist() == oracle_mod.discretize(v[b].tolist(), int(budget[b]), M), (k, b)
+    assert outs["wabar"][0, 0].item() == M
+
+
+def test_discretize_optional_arrays_left_alone(amd):
+    import torch
+    L, M, B = 5, 16, 2
+    z = lambda n: torch.ones((B, n), dtype=torch.int64, device="cuda")
+    wa = torch.full((B, L + 1), -1, dtype=torch.int32, device="cuda")
+    wabar = torch.full((B, L), -1, dtype=torch.int32, device="cuda")
+    amd.ckpt_discretize(z(L + 1), z(L), torch.full((B,), 16, dtype=torch.int64, device="cuda"), L, M, B, wa, wabar)
+    assert (wa == 1).all() and (wabar == 1).all()
+
+
+def test_schedule_batched_matches_host_walk_and_oracle(amd, oracle_mod, solved):
+    import torch
+    batch, sol, tables = solved
+    L, M, B = batch.L, batch.M, batch.B
+    cap = L * (L + 1) // 2 + L
+    wa = torch.from_numpy(batch.wa).cuda()
+    wabar = torch.from_numpy(batch.wabar).cuda()
+    ws = torch.empty(amd.ckpt_schedule_workspace_bytes(L, B), dtype=torch.uint8, device="cuda")
+    arg_host = sol.arg.cpu().numpy()
+    for name, budgets in _budget_sets(batch, tables, oracle_mod):
+        ops = torch.zeros((B, cap, 2), dtype=torch.uint8, device="cuda")
+        n_ops = torch.zeros(B, dtype=torch.int32, device="cuda")
+        amd.ckpt_schedule_batched(sol.arg, wa, wabar, L, M, B, torch.tensor(budgets, dtype=torch.int32, device="cuda"),
+                                  ops, cap, n_ops, ws)
+        ops_h, n_h = ops.cpu().numpy(), n_ops.cpu().numpy()
+        for b in range(B):
+            m = budgets[b]
+            if m < 0:
+                assert n_h[b] == -1, (name, b)
+                continue
+            m = min(m, M)
+            if tables[b][0][0, L - 1, m] >= oracle_mod.INF:
+                assert n_h[b] == -3, (name, b)
+                continue
+            want = oracle_mod.reconstruct(tables[b][1], batch.wa[b], batch.wabar[b], 1, L, m)
+            got = [tuple(x) for x in ops_h[b, :n_h[b]].tolist()]
+            assert got == want, (name, b)
+            assert got == amd.ckpt_schedule(arg_host[b], batch.wa[b], batch.wabar[b], L, M, 1, L, m), (name, b)
+
+
+def test_schedule_batched_small_capacity_and_corrupt_table(amd, solved):
+    import torch
+    batch, sol, _ = solved
+    L, M, B = batch.L, batch.M, batch.B
+    wa = torch.from_numpy(batch.wa).cuda()
+    wabar = torch.from_numpy(batch.wabar).cuda()
+    ws = torch.empty(amd.ckpt_schedule_workspace_bytes(L, B), dtype=torch.uint8, device="cuda")
+    budgets = torch.full((B,), M, dtype=torch.int32, device="cuda")
+    ops = torch.zeros((B, 5, 2), dtype=torch.uint8, device="cuda")
+    n_ops = torch.zeros(B, dtype=torch.int32, device="cuda")
+    amd.ckpt_schedule_batched(sol.arg, wa, wabar, L, M, B, budgets, ops, 5, n_ops, ws)
+    assert (n_ops == -4).all()
+    broken = sol.arg.clone()
+    broken[3, amd.ckpt_row_index(L, 1, L), M] = L + 9
+    cap = L * (L + 1) // 2 + L
+    ops = torch.zeros((B, cap, 2), dtype=torch.uint8, device="cuda")
+    amd.ckpt_schedule_batched(broken, wa, wabar, L, M, B, budgets, ops, cap, n_ops, ws)
+    got = n_ops.cpu().tolist()
+    assert got[3] == -7 and all(v > 0 for k, v in enumerate(got) if k != 3)
