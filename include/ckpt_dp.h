@@ -34,10 +34,13 @@
  *   columns 0..M; columns M+1..pitch-1 are padding with unspecified contents.
  *   Rows are ordered by s, then t:  index = (s-1)*L - (s-1)*(s-2)/2 + (t-s).
  *
- * Ownership and threading: the library keeps no global state besides the last HIP
- * error code; every buffer belongs to the caller and must stay valid until the
- * work enqueued on the stream has finished.  Calls on different streams with
- * disjoint buffers are independent.
+ * Ownership and threading: every buffer belongs to the caller and must stay valid
+ * until the work enqueued on the stream has finished.  The library's only state is the
+ * last HIP error code and, per device, one helper stream with two events that
+ * ckpt_solve_batched creates on its first call there and keeps (it runs half of a
+ * batch on it, forked from and joined back into the caller's stream).  Calls from
+ * several threads and on different streams with disjoint buffers are safe; their
+ * enqueueing is serialised per device.
  *
  * Errors: every function that can fail returns CKPT_OK (0) or a negative code and
  * never throws or aborts.  Argument errors are reported before anything is
@@ -59,7 +62,7 @@ extern "C" {
 enum {
     CKPT_OK = 0,
     CKPT_E_ARG = -1,        /* null pointer, L < 1, M < 0, B < 1, s/t/m out of range */
-    CKPT_E_LIMIT = -2,      /* L > CKPT_MAX_L, or rows*pitch >= 2^30 elements per chain */
+    CKPT_E_LIMIT = -2,      /* L > CKPT_MAX_L, rows*pitch >= 2^30 elements per chain, B > 65535 */
     CKPT_E_INFEASIBLE = -3, /* ckpt_schedule: the requested cell is infeasible */
     CKPT_E_SMALLBUF = -4,   /* ckpt_schedule: ops_cap too small (2L-1 .. L(L+1)/2+L operations) */
     CKPT_E_HIP = -5,        /* a HIP call failed; see ckpt_last_hip_error() */
@@ -109,7 +112,8 @@ size_t ckpt_workspace_bytes(int L, int M, int B);
  *   chains    host pointer to a struct of DEVICE pointers (read during the call
  *             only; the arrays it names are read by the enqueued kernels)
  *   stream    a hipStream_t (NULL = the default stream); the call only enqueues
- *             work and returns, it does not synchronise and allocates nothing
+ *             work and returns, it does not synchronise and allocates no memory
+ *             (see the helper stream above); it may be captured into a HIP graph
  *   cost, arg DEVICE tables laid out as above, 256-byte aligned
  *   workspace DEVICE memory of ckpt_workspace_bytes(L, M, B) bytes, 256-byte
  *             aligned; holds per-chain prefix sums, thresholds and input flags

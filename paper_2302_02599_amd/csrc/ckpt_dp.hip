@@ -10,6 +10,7 @@
 #include <utility>
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 #include <vector>
 
 #include "ckpt_dp.h"
@@ -104,6 +105,7 @@ inline Workspace carve(void* base, int L, int B) {
 
 struct Ctx {
     int L, M, pitch, rows;
+    int b0;  // first chain of this launch; blockIdx.z counts from it
     Workspace ws;
     int32_t* cost;
     uint8_t* arg;
@@ -261,7 +263,7 @@ template <int NB, int UNR, int CH>
 __global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
     constexpr int T = kT;
     static_assert(T == 8, "one wave per 8x8 tile");
-    const int b = blockIdx.z, I = blockIdx.y, J = I + D;
+    const int b = c.b0 + blockIdx.z, I = blockIdx.y, J = I + D;
     const int L = c.L, pitch = c.pitch;
     const int qlo = (I + 1) * T, qhi = J * T;
     const int j0 = J * T, i0 = I * T;
@@ -404,7 +406,7 @@ __global__ void __launch_bounds__(256) row_kernel(Ctx c, int D) {
     constexpr int CF = (DC == 0) ? R : 0;                              // first column with j >= i
     constexpr int NQ = (DC == 0) ? 0 : (DC == 1 ? T - R : T - 1 - R);  // near-i splits (D = 1: and q = jb)
     constexpr int NQA = NQ > 0 ? NQ : 1;
-    const int b = blockIdx.z, I = blockIdx.y, J = I + D;
+    const int b = c.b0 + blockIdx.z, I = blockIdx.y, J = I + D;
     const int L = c.L, pitch = c.pitch;
     const int i = I * T + R;
     if (i >= L) return;
@@ -637,6 +639,7 @@ int check_dims(int L, int M, int B) {
     if (L > CKPT_MAX_L) return CKPT_E_LIMIT;
     const unsigned long long per_chain = (unsigned long long)ckpt_table_rows(L) * ckpt_row_pitch(M);
     if (per_chain >= (1ull << 30)) return CKPT_E_LIMIT;  // 4 GiB of int32 per chain
+    if (B > 65535) return CKPT_E_LIMIT;                   // chains are the z dimension of the grids
     return CKPT_OK;
 }
 
@@ -660,6 +663,31 @@ struct Profile {
         if (prof && !prof->mark(kind)) return CKPT_E_HIP;         \
     } while (0)
 
+// Second stream of the two-way batch split, one per device, created on first use and kept
+// for the life of the process (default priority, non-blocking).
+struct Side {
+    hipStream_t stream = nullptr;
+    hipEvent_t fork = nullptr, join = nullptr;
+    bool tried = false, ok = false;
+    std::mutex busy;
+};
+
+Side* side_streams() {
+    static Side table[64];
+    static std::mutex init;
+    int dev = 0;
+    if (!hip_ok(hipGetDevice(&dev)) || dev < 0 || dev >= 64) return nullptr;
+    Side& s = table[dev];
+    std::lock_guard<std::mutex> guard(init);
+    if (!s.tried) {
+        s.tried = true;
+        s.ok = hip_ok(hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking)) &&
+               hip_ok(hipEventCreateWithFlags(&s.fork, hipEventDisableTiming)) &&
+               hip_ok(hipEventCreateWithFlags(&s.join, hipEventDisableTiming));
+    }
+    return s.ok ? &s : nullptr;
+}
+
 int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost, uint8_t* arg,
                void* workspace, Profile* prof) {
     if (!chains || !cost || !arg || !workspace) return CKPT_E_ARG;
@@ -676,28 +704,58 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     const size_t frontier_lds = ckpt_table_rows(L) * sizeof(int32_t);
     if (frontier_lds > 48 * 1024) {
         // Above the default per-block limit the kernel has to be allowed its LDS size; this sets a
-        // function attribute and allocates nothing.
+        // function attribute (to the largest size any L can need) and allocates nothing.
         if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(precompute_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize, int(frontier_lds))))
+                                        hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        int(ckpt_table_rows(CKPT_MAX_L) * sizeof(int32_t)))))
             return CKPT_E_HIP;
     }
     hipLaunchKernelGGL(precompute_kernel, dim3(B), dim3(1024), frontier_lds, st, *chains, L, pitch, ws);
     CKPT_AFTER_LAUNCH(CKPT_K_PRECOMPUTE);
-    const Ctx ctx{L, M, pitch, rows, ws, cost, arg};
     constexpr int T = kT;
     const int nblk = (L + T - 1) / T;
-    const int gx_gemm = pitch / 64, gx_row = (pitch + 255) / 256;
+    const int gx_gemm = (pitch / 64 + kCH - 1) / kCH, gx_row = (pitch + 255) / 256;
+
+    // Chains are independent, so the batch is split in two halves that run the same launch
+    // sequence on two streams: the many short row launches of one half overlap with work of the
+    // other half instead of leaving the machine idle between dependent launches.  The second
+    // stream is forked from and joined back into the caller's stream with events.
+    int groups = 1;
+    Side* side = nullptr;
+    std::unique_lock<std::mutex> lock;
+    if (!prof && B >= 2 && nblk >= 3) {
+        side = side_streams();
+        if (side) {
+            lock = std::unique_lock<std::mutex>(side->busy);  // one fork/join at a time per device
+            if (!hip_ok(hipEventRecord(side->fork, st)) || !hip_ok(hipStreamWaitEvent(side->stream, side->fork, 0)))
+                return CKPT_E_HIP;
+            groups = 2;
+        }
+    }
+    const int first[3] = {0, groups == 2 ? B / 2 : B, B};
+    hipStream_t gs[2] = {st, side ? side->stream : st};
     for (int D = 0; D < nblk; ++D) {
-        const dim3 tiles_gemm(gx_gemm, nblk - D, B), tiles_row(gx_row, nblk - D, B);
         if (D >= 2) {
-            hipLaunchKernelGGL((gemm_kernel<3, 3, kCH>), dim3((gx_gemm + kCH - 1) / kCH, nblk - D, B), dim3(64 * kCH), 0, st, ctx, D);
-            CKPT_AFTER_LAUNCH(CKPT_K_GEMM);
+            for (int g = 0; g < groups; ++g) {
+                const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
+                hipLaunchKernelGGL((gemm_kernel<3, 3, kCH>), dim3(gx_gemm, nblk - D, first[g + 1] - first[g]),
+                                   dim3(64 * kCH), 0, gs[g], ctx, D);
+                CKPT_AFTER_LAUNCH(CKPT_K_GEMM);
+            }
         }
         const auto& rowfn = D == 0 ? kRow0 : (D == 1 ? kRow1 : kRow2);
         for (int r = T - 1; r >= 0; --r) {
-            hipLaunchKernelGGL(rowfn[r], tiles_row, dim3(256), 0, st, ctx, D);
-            CKPT_AFTER_LAUNCH(CKPT_K_ROW);
+            for (int g = 0; g < groups; ++g) {
+                const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
+                hipLaunchKernelGGL(rowfn[r], dim3(gx_row, nblk - D, first[g + 1] - first[g]), dim3(256), 0, gs[g],
+                                   ctx, D);
+                CKPT_AFTER_LAUNCH(CKPT_K_ROW);
+            }
         }
+    }
+    if (groups == 2) {
+        if (!hip_ok(hipEventRecord(side->join, side->stream)) || !hip_ok(hipStreamWaitEvent(st, side->join, 0)))
+            return CKPT_E_HIP;
     }
     return CKPT_OK;
 }

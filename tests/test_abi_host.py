@@ -59,6 +59,7 @@ def test_solve_rejects_bad_arguments_before_touching_the_gpu(amd):
     assert f(ctypes.byref(ch), 4, 8, 0, None, 256, 256, 256) == -1
     assert f(ctypes.byref(ch), 255, 8, 1, None, 256, 256, 256) == -2          # arg is one byte
     assert f(ctypes.byref(ch), 254, 2 ** 16, 1, None, 256, 256, 256) == -2    # chain table of 4 GiB or more
+    assert f(ctypes.byref(ch), 4, 8, 65536, None, 256, 256, 256) == -2         # more chains than a grid dimension
     assert f(ctypes.byref(ch), 4, 8, 1, None, 260, 256, 256) == -1            # misaligned table
     assert f(ctypes.byref(ch), 4, 8, 1, None, None, 256, 256) == -1
     ch2 = _Chains(256, None, 256, 256, None, None, None)

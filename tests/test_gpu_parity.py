@@ -39,6 +39,7 @@ def test_configs_small(amd, oracle_mod, cfg):
     (33, 97, 5, 13, True, False, False), (40, 1, 2, 14, False, False, False),
     (50, 130, 2, 15, True, True, False), (57, 66, 3, 16, False, False, False), (71, 190, 1, 17, True, True, False),
     (64, 64, 2, 18, False, True, False), (100, 70, 1, 19, True, False, False),
+    (254, 130, 1, 20, True, True, False), (192, 300, 2, 21, False, False, False),
 ])
 def test_ragged_shapes(amd, oracle_mod, L, M, B, seed, ovh, wd, zero):
     """Chain lengths and budgets that are not multiples of any tile, incl. M = 0 and L = 1."""
@@ -136,6 +137,52 @@ def test_solve_on_a_side_stream(amd, oracle_mod):
         sol = amd.solve(batch)
     st.synchronize()
     assert_tables_equal(oracle_mod, batch, sol)
+
+
+def test_solve_can_be_captured_in_a_hip_graph(amd):
+    """Capture one solve (including the internal fork/join onto the second stream), replay it several
+    times with eager work and synchronisations in between, and compare every replay with the eager tables."""
+    import torch
+    batch = make_config(2)
+    L, M, B = batch.L, batch.M, batch.B
+    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    uf, ub, wa, wabar = up(batch.uf), up(batch.ub), up(batch.wa), up(batch.wabar)
+    cost = torch.empty(amd.ckpt_table_elems(L, M, B), dtype=torch.int32, device="cuda")
+    arg = torch.empty(amd.ckpt_table_elems(L, M, B), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(amd.ckpt_workspace_bytes(L, M, B), dtype=torch.uint8, device="cuda")
+    eager = amd.solve(batch)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        amd.ckpt_solve_batched(uf, ub, wa, wabar, L, M, B, cost, arg, ws)      # warm-up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        amd.ckpt_solve_batched(uf, ub, wa, wabar, L, M, B, cost, arg, ws)
+    torch.cuda.synchronize()
+    pitch = amd.ckpt_row_pitch(M)
+    for _ in range(3):
+        cost.fill_(-5)
+        arg.fill_(77)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert (cost.view(B, -1, pitch)[:, :, :M + 1] == eager.cost[:, :, :M + 1]).all()
+        assert (arg.view(B, -1, pitch)[:, :, :M + 1] == eager.arg[:, :, :M + 1]).all()
+
+
+def test_concurrent_solves_on_two_streams(amd, oracle_mod):
+    """Two solves in flight at once on different caller streams share the library's second stream."""
+    import torch
+    b1, b2 = make_config(2), random_chain_batch(40, 300, 4, 33, size_hi=9, overheads=True)
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    with torch.cuda.stream(s1):
+        sol1 = amd.solve(b1, check=False)
+    with torch.cuda.stream(s2):
+        sol2 = amd.solve(b2, check=False)
+    torch.cuda.synchronize()
+    assert_tables_equal(oracle_mod, b1, sol1, nthreads=8, chains=[0, 7, 15])
+    assert_tables_equal(oracle_mod, b2, sol2, nthreads=4)
 
 
 def _full_solution(amd, cfg):
