@@ -131,7 +131,7 @@ int ckpt_solve_batched(const ckpt_chains_t* chains, int L, int M, int B, void* s
  * Creates and destroys events (allocates); not for latency-critical callers.
  * Returns as ckpt_solve_batched.
  */
-enum { CKPT_K_PRECOMPUTE = 0, CKPT_K_GEMM = 1, CKPT_K_ROW = 2, CKPT_N_KERNEL_KINDS = 3 };
+enum { CKPT_K_PRECOMPUTE = 0, CKPT_K_FRONTIER = 1, CKPT_K_GEMM = 2, CKPT_K_ROW = 3, CKPT_N_KERNEL_KINDS = 4 };
 int ckpt_solve_profiled(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
                         uint8_t* arg, void* workspace, float* kind_ms, int* kind_launches);
 /* Name of a kernel kind as it appears in a rocprofv3 kernel trace; NULL if out of range. */

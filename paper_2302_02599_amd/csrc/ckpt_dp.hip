@@ -115,16 +115,9 @@ __host__ __device__ inline int tri_row(int L, int i, int j) {  // 0-based i <= j
     return i * L - (i * (i - 1)) / 2 + (j - i);
 }
 
-// One block per chain: input checks, prefix sums, shifts, both threshold tables (last
-// display of the Theorem) and the feasibility frontier need[i][j] = smallest m at which
-// cell (i, j) can be finite.
-//
-// The frontier follows the recurrence with costs dropped: a leaf needs m_all; keeping
-// abar^s needs max(m_all, omega_abar^s + need(s+1, t)); a checkpoint split at q needs
-// max(m_null, omega_a^q + need(q, t), need(s, q-1)).  A cell below its frontier is
-// infeasible whatever the times are, so the fill kernels skip work there.  Values
-// saturate at 2^30, above any admissible M.
-__global__ void __launch_bounds__(1024) precompute_kernel(ckpt_chains_t ch, int L, int pitch, Workspace ws) {
+// One block per chain: input checks, prefix sums, shifts and both threshold tables (last
+// display of the Theorem).
+__global__ void __launch_bounds__(256) precompute_kernel(ckpt_chains_t ch, int L, int pitch, Workspace ws) {
     const int b = blockIdx.x;
     const int tid = threadIdx.x;
     const int32_t* uf = ch.uf + size_t(b) * L;
@@ -176,25 +169,44 @@ __global__ void __launch_bounds__(1024) precompute_kernel(ckpt_chains_t ch, int 
         }
         ws.flags[b] = flags;
     }
+    // thresholds: sizes staged in LDS, thread s builds row s with a running maximum over t
+    __shared__ int32_t s_wa[CKPT_MAX_L + 2], s_wd[CKPT_MAX_L + 2], s_of[CKPT_MAX_L + 2];
+    for (int k = tid; k <= L; k += blockDim.x) {
+        s_wa[k] = sz(wa[k]);
+        s_wd[k] = sz(wd[k]);
+        s_of[k] = (of && k < L) ? sz(of[k]) : 0;
+    }
+    __syncthreads();
     for (int s0 = tid; s0 < L; s0 += blockDim.x) {
         const int s = s0 + 1;
-        const int ofs = of ? sz(of[s0]) : 0, obs = ob ? sz(ob[s0]) : 0;
-        int sweep = sz(wa[s]) + ofs;  // omega_a^s + o_f^s, then max over s+1 <= j < t
+        const int ofs = s_of[s0], obs = ob ? sz(ob[s0]) : 0, abar = sz(wab[s0]);
+        int sweep = s_wa[s] + ofs;  // omega_a^s + o_f^s, then max over s+1 <= j < t
         int32_t* mall = ws.mall + (size_t(b) * L + s0) * L;
         int32_t* mnull = ws.mnull + (size_t(b) * L + s0) * L;
         for (int t = s; t <= L; ++t) {
             if (t >= s + 2) {
                 const int j = t - 1;
-                sweep = max(sweep, sz(wa[j - 1]) + sz(wa[j]) + (of ? sz(of[j - 1]) : 0));
+                sweep = max(sweep, s_wa[j - 1] + s_wa[j] + s_of[j - 1]);
             }
-            mall[t - 1] = max(sz(wd[t]) + sz(wab[s0]) + ofs, sz(wd[s]) + sz(wab[s0]) + obs);
-            mnull[t - 1] = sz(wd[t]) + sweep;
+            mall[t - 1] = max(s_wd[t] + abar + ofs, s_wd[s] + abar + obs);
+            mnull[t - 1] = s_wd[t] + sweep;
         }
     }
-    __syncthreads();
+}
 
-    // Feasibility frontier, one segment length at a time.  The triangle lives in LDS (row-major
-    // packed, L(L+1)/2 ints <= 127 KiB); 16 lanes share the splits of one cell.
+// Feasibility frontier need[i][j] = smallest m at which cell (i, j) can be finite: the
+// recurrence with costs dropped.  A leaf needs m_all; keeping abar^s needs
+// max(m_all, omega_abar^s + need(s+1, t)); a checkpoint split at q needs
+// max(m_null, omega_a^q + need(q, t), need(s, q-1)).  A cell below its frontier is infeasible
+// whatever the times are, so the fill kernels skip work there.  Values saturate at 2^30,
+// above any admissible M.  One block per chain, one segment length at a time; the triangle
+// lives in LDS (row-major packed, L(L+1)/2 ints <= 127 KiB); 16 lanes share the splits of a cell.
+__global__ void __launch_bounds__(1024) frontier_kernel(ckpt_chains_t ch, int L, Workspace ws) {
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int32_t* wa = ch.wa + size_t(b) * (L + 1);
+    const int32_t* wab = ch.wabar + size_t(b) * L;
+    auto sz = [](int v) { return min(max(v, 0), 1 << 28); };
     extern __shared__ int32_t s_need[];
     __shared__ int32_t s_wa[CKPT_MAX_L + 2];
     __shared__ int32_t s_wab[CKPT_MAX_L + 2];
@@ -435,10 +447,13 @@ __global__ void __launch_bounds__(256) row_kernel(Ctx c, int D) {
     // A wave whose whole chunk lies below the feasibility frontier of every cell of the row
     // stores "infeasible" and reads nothing.
     {
+        // D >= 2: the frontier.  D < 2 runs while the frontier is still being computed and uses the
+        // weaker bound min(m_all, m_null): a finite cell passes at least one of its two gates.
         const int32_t* need = c.ws.need + (size_t(b) * L + i) * L;
         int row_need = 1 << 30;
 #pragma unroll
-        for (int cc = CF; cc < T; ++cc) row_need = min(row_need, need[jc[cc]]);
+        for (int cc = CF; cc < T; ++cc)
+            row_need = min(row_need, DC == 2 ? need[jc[cc]] : min(mall[jc[cc]], mnull[jc[cc]]));
         const int m_hi = __builtin_amdgcn_readfirstlane(int(m)) | 63;
         if (m_hi < row_need) {
 #pragma unroll
@@ -705,45 +720,62 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     if (frontier_lds > 48 * 1024) {
         // Above the default per-block limit the kernel has to be allowed its LDS size; this sets a
         // function attribute (to the largest size any L can need) and allocates nothing.
-        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(precompute_kernel),
+        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(frontier_kernel),
                                         hipFuncAttributeMaxDynamicSharedMemorySize,
                                         int(ckpt_table_rows(CKPT_MAX_L) * sizeof(int32_t)))))
             return CKPT_E_HIP;
     }
-    hipLaunchKernelGGL(precompute_kernel, dim3(B), dim3(1024), frontier_lds, st, *chains, L, pitch, ws);
-    CKPT_AFTER_LAUNCH(CKPT_K_PRECOMPUTE);
     constexpr int T = kT;
     const int nblk = (L + T - 1) / T;
     const int gx_gemm = (pitch / 64 + kCH - 1) / kCH, gx_row = (pitch + 255) / 256;
 
-    // Chains are independent, so the batch is split in two halves that run the same launch
-    // sequence on two streams: the many short row launches of one half overlap with work of the
-    // other half instead of leaving the machine idle between dependent launches.  The second
-    // stream is forked from and joined back into the caller's stream with events.
-    int groups = 1;
-    Side* side = nullptr;
+    // Two streams.  Chains are independent, so from D = 2 on the batch is split in two halves
+    // that run the same launch sequence on two streams: the many short row launches of one half
+    // overlap with work of the other half instead of leaving the machine idle between dependent
+    // launches.  Before that, the frontier (a few busy CUs for a long time) runs on the second
+    // stream next to the D = 0 and D = 1 rows of the whole batch, which do not need it.  The
+    // second stream is forked from and joined back into the caller's stream with events.
+    Side* side = (!prof && B >= 2 && nblk >= 3) ? side_streams() : nullptr;
     std::unique_lock<std::mutex> lock;
-    if (!prof && B >= 2 && nblk >= 3) {
-        side = side_streams();
-        if (side) {
-            lock = std::unique_lock<std::mutex>(side->busy);  // one fork/join at a time per device
-            if (!hip_ok(hipEventRecord(side->fork, st)) || !hip_ok(hipStreamWaitEvent(side->stream, side->fork, 0)))
-                return CKPT_E_HIP;
-            groups = 2;
-        }
-    }
-    const int first[3] = {0, groups == 2 ? B / 2 : B, B};
-    hipStream_t gs[2] = {st, side ? side->stream : st};
-    for (int D = 0; D < nblk; ++D) {
-        if (D >= 2) {
-            for (int g = 0; g < groups; ++g) {
-                const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
-                hipLaunchKernelGGL((gemm_kernel<3, 3, kCH>), dim3(gx_gemm, nblk - D, first[g + 1] - first[g]),
-                                   dim3(64 * kCH), 0, gs[g], ctx, D);
-                CKPT_AFTER_LAUNCH(CKPT_K_GEMM);
-            }
-        }
+    if (side) lock = std::unique_lock<std::mutex>(side->busy);  // one fork/join at a time per device
+    hipStream_t s2 = side ? side->stream : st;
+
+    hipLaunchKernelGGL(precompute_kernel, dim3(B), dim3(256), 0, st, *chains, L, pitch, ws);
+    CKPT_AFTER_LAUNCH(CKPT_K_PRECOMPUTE);
+    if (side && (!hip_ok(hipEventRecord(side->fork, st)) || !hip_ok(hipStreamWaitEvent(s2, side->fork, 0))))
+        return CKPT_E_HIP;
+    hipLaunchKernelGGL(frontier_kernel, dim3(B), dim3(1024), frontier_lds, s2, *chains, L, ws);
+    CKPT_AFTER_LAUNCH(CKPT_K_FRONTIER);
+
+    auto launch_rows = [&](int D, int b0, int nb, hipStream_t s) -> int {
+        const Ctx ctx{L, M, pitch, rows, b0, ws, cost, arg};
         const auto& rowfn = D == 0 ? kRow0 : (D == 1 ? kRow1 : kRow2);
+        for (int r = T - 1; r >= 0; --r) {
+            hipLaunchKernelGGL(rowfn[r], dim3(gx_row, nblk - D, nb), dim3(256), 0, s, ctx, D);
+            CKPT_AFTER_LAUNCH(CKPT_K_ROW);
+        }
+        return CKPT_OK;
+    };
+    for (int D = 0; D < 2 && D < nblk; ++D)
+        if (int rc = launch_rows(D, 0, B, st)) return rc;
+    if (side) {
+        // both streams wait for each other: the frontier is done, and so are the D < 2 rows
+        if (!hip_ok(hipEventRecord(side->join, s2)) || !hip_ok(hipStreamWaitEvent(st, side->join, 0)) ||
+            !hip_ok(hipEventRecord(side->fork, st)) || !hip_ok(hipStreamWaitEvent(s2, side->fork, 0)))
+            return CKPT_E_HIP;
+    }
+    const int groups = side ? 2 : 1;
+    const int first[3] = {0, side ? B / 2 : B, B};
+    hipStream_t gs[2] = {st, s2};
+    for (int D = 2; D < nblk; ++D) {
+        for (int g = 0; g < groups; ++g) {
+            const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
+            hipLaunchKernelGGL((gemm_kernel<3, 3, kCH>), dim3(gx_gemm, nblk - D, first[g + 1] - first[g]),
+                               dim3(64 * kCH), 0, gs[g], ctx, D);
+            CKPT_AFTER_LAUNCH(CKPT_K_GEMM);
+        }
+        // rows of the two halves are issued alternately so that both queues stay fed
+        const auto& rowfn = kRow2;
         for (int r = T - 1; r >= 0; --r) {
             for (int g = 0; g < groups; ++g) {
                 const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
@@ -753,8 +785,8 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
             }
         }
     }
-    if (groups == 2) {
-        if (!hip_ok(hipEventRecord(side->join, side->stream)) || !hip_ok(hipStreamWaitEvent(st, side->join, 0)))
+    if (side) {
+        if (!hip_ok(hipEventRecord(side->join, s2)) || !hip_ok(hipStreamWaitEvent(st, side->join, 0)))
             return CKPT_E_HIP;
     }
     return CKPT_OK;
@@ -812,6 +844,7 @@ int ckpt_solve_profiled(const ckpt_chains_t* chains, int L, int M, int B, void* 
 const char* ckpt_kernel_name(int kind) {
     switch (kind) {
         case CKPT_K_PRECOMPUTE: return "precompute_kernel";
+        case CKPT_K_FRONTIER: return "frontier_kernel";
         case CKPT_K_GEMM: return "gemm_kernel";
         case CKPT_K_ROW: return "row_kernel";
         default: return nullptr;
