@@ -209,6 +209,32 @@ int ckpt_schedule_batched(const uint8_t* arg, const int32_t* wa, const int32_t* 
 /* Bytes of DEVICE workspace (16-byte aligned) ckpt_schedule_batched needs: the walk stacks. */
 size_t ckpt_schedule_workspace_bytes(int L, int B);
 
+/*
+ * Network linearisation on the host (Sections "Linearization", "Common Node" and the
+ * algorithm of "Full Set of Linearization Rules"): cuts a computation DAG into the node
+ * groups that become the stages of a chain.
+ *   n, child_ptr[n+1], child_idx   HOST CSR adjacency; nodes are numbered in topological
+ *                                  order (every child index is larger than its parent's)
+ *   flags[n]                       HOST CKPT_NODE_* bit sets
+ *   group_of_node[n]               HOST out: group index 0.., -1 for placeholders
+ *   is_common[n]                   HOST out: 1 if the node is a common node (seeded, or its
+ *                                  operation is non-differentiable, or all its parents are common)
+ * A node ends a group when, after releasing one dependency of each of its parents that is
+ * neither placeholder nor common, no dependency is pending and none of its children is an
+ * in-place or communication operation; a node that is not common then registers one
+ * dependency per non-placeholder child.  Nodes left after the last cut form a final group.
+ * Returns the number of groups, or CKPT_E_ARG (bad pointers, edges that are not forward).
+ */
+enum {
+    CKPT_NODE_PLACEHOLDER = 1, /* network input or output */
+    CKPT_NODE_COMMON_SEED = 2, /* non-differentiable input, e.g. an attention mask */
+    CKPT_NODE_NON_DIFF = 4,    /* non-differentiable operation, e.g. getattr, getitem */
+    CKPT_NODE_IN_PLACE = 8,    /* in-place operation: stays with its parent */
+    CKPT_NODE_COMM = 16        /* communication operation: stays with its parent */
+};
+int ckpt_linearize(int n, const int32_t* child_ptr, const int32_t* child_idx, const uint8_t* flags,
+                   int32_t* group_of_node, uint8_t* is_common);
+
 /* hipError_t of the most recent failed HIP call made by this library (0 if none). */
 int ckpt_last_hip_error(void);
 /* Static description of a CKPT_* code. */

@@ -198,3 +198,64 @@ def discretize(sizes_bytes, budget_bytes, M):
             raise ValueError("negative size")
         out.append(min(SLOT_MAX, -((-v * M) // budget)))
     return out
+
+
+# Node flags of the linearisation input (one byte per node).
+PLACEHOLDER, COMMON_SEED, NON_DIFF, IN_PLACE, COMM = 1, 2, 4, 8, 16
+
+
+def linearize(children, flags):
+    """Network linearisation, Algorithm "network linearization algorithm" with the definitions of
+    Sections "Linearization" and "Common Node".
+
+    Nodes 0..n-1 are in topological order; children[v] lists the children of v; flags[v] is a
+    bit set of PLACEHOLDER (network input/output), COMMON_SEED (a non-differentiable input such
+    as an attention mask), NON_DIFF (non-differentiable operation such as getattr/getitem),
+    IN_PLACE, COMM (communication operation).
+
+    Steps, in the paper's order, for every node that is not a placeholder: release one
+    dependency of each parent that is neither a placeholder nor a common node; append the node
+    to the current group; if the pool of pending dependencies is empty and no child of the node
+    is an in-place or communication operation, close the group; then either label the node
+    common (its operation is non-differentiable, or all of its parents are common) or put its
+    own dependencies (one per child that will be examined, i.e. not a placeholder) in the pool.
+
+    Returns (group index per node, -1 for placeholders; common flag per node; number of groups).
+    Nodes left over after the last closed group form a final group.
+    """
+    n = len(children)
+    parents = [[] for _ in range(n)]
+    for v in range(n):
+        for c in children[v]:
+            parents[c].append(v)
+    common = [bool(flags[v] & COMMON_SEED) for v in range(n)]
+    pool = {}
+    group = [-1] * n
+    current = []
+    ngroups = 0
+    for v in range(n):
+        if flags[v] & PLACEHOLDER:
+            continue
+        for p in parents[v]:
+            if not (flags[p] & PLACEHOLDER) and not common[p]:
+                pool[p] -= 1
+                if pool[p] == 0:
+                    del pool[p]
+        current.append(v)
+        sticky = any(flags[c] & (IN_PLACE | COMM) for c in children[v])
+        if not pool and not sticky:
+            for u in current:
+                group[u] = ngroups
+            ngroups += 1
+            current = []
+        if (flags[v] & NON_DIFF) or all(common[p] for p in parents[v]):
+            common[v] = True
+        else:
+            deps = sum(1 for c in children[v] if not flags[c] & PLACEHOLDER)
+            if deps:
+                pool[v] = deps
+    if current:
+        for u in current:
+            group[u] = ngroups
+        ngroups += 1
+    return group, common, ngroups

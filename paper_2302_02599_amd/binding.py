@@ -69,6 +69,8 @@ def load_library():
     lib.ckpt_schedule_batched.restype = i
     lib.ckpt_schedule_batched.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp, i, vp, vp]
     lib.ckpt_schedule_workspace_bytes.restype, lib.ckpt_schedule_workspace_bytes.argtypes = sz, [i, i]
+    lib.ckpt_linearize.restype = i
+    lib.ckpt_linearize.argtypes = [i, vp, vp, vp, vp, vp]
     lib.ckpt_last_hip_error.restype, lib.ckpt_last_hip_error.argtypes = i, []
     lib.ckpt_strerror.restype, lib.ckpt_strerror.argtypes = ctypes.c_char_p, [i]
     _lib = lib
@@ -236,6 +238,23 @@ def ckpt_schedule_batched(arg, wa, wabar, L, M, B, m_budget, ops, ops_cap, n_ops
         _dev(workspace, "workspace", torch.uint8, ckpt_schedule_workspace_bytes(L, B)))
     if rc != 0:
         raise CkptError(rc, "ckpt_schedule_batched")
+
+
+def ckpt_linearize(children, flags):
+    """Host linearisation of a DAG given as per-node child lists in topological order.
+    Returns (group index per node, common flag per node, number of groups)."""
+    n = len(children)
+    ptr = np.zeros(n + 1, np.int32)
+    ptr[1:] = np.cumsum([len(c) for c in children])
+    idx = np.array([c for cs in children for c in cs], np.int32)
+    fl = np.ascontiguousarray(flags, dtype=np.uint8)
+    group = np.empty(max(n, 1), np.int32)
+    common = np.empty(max(n, 1), np.uint8)
+    rc = load_library().ckpt_linearize(n, ptr.ctypes.data, idx.ctypes.data if idx.size else None, fl.ctypes.data,
+                                       group.ctypes.data, common.ctypes.data)
+    if rc < 0:
+        raise CkptError(rc, "ckpt_linearize")
+    return group[:n].tolist(), [bool(c) for c in common[:n]], rc
 
 
 @dataclass
