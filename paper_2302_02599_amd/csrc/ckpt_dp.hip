@@ -11,6 +11,7 @@
 #include <cstdint>
 #include <cstring>
 #include <mutex>
+#include <type_traits>
 #include <vector>
 
 #include "ckpt_dp.h"
@@ -374,18 +375,22 @@ __global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
 #pragma unroll
         for (int u = 0; u < NB - 1; ++u) load(buf[u], min(u, n - 1));
         constexpr int STEPS = NB * UNR;
-        const int iters = (n + STEPS - 1) / STEPS;
-        int k = 0;
-        for (int it = 0; it < iters; ++it) {
+        auto steps = [&](auto count, int& k) {  // count.value pipeline steps, straight-line
 #pragma unroll
-            for (int u = 0; u < STEPS; ++u) {
+            for (int u = 0; u < decltype(count)::value; ++u) {
                 load(buf[(u + NB - 1) % NB], min(k + NB - 1, n - 1));
                 __builtin_amdgcn_sched_barrier(0);  // keep these loads ahead of the math of entry k
                 compute(buf[u % NB], min(k, n - 1));
                 __builtin_amdgcn_sched_barrier(0);
                 ++k;
             }
-        }
+        };
+        // long body for the bulk (the compiler's wait at a loop header is conservative, so few
+        // headers), then the remainder in bodies of NB steps: at most NB - 1 padded entries
+        int k = 0;
+        const int bulk = n / STEPS, tail = (n - bulk * STEPS + NB - 1) / NB;
+        for (int it = 0; it < bulk; ++it) steps(std::integral_constant<int, STEPS>{}, k);
+        for (int it = 0; it < tail; ++it) steps(std::integral_constant<int, NB>{}, k);
     }
 
     const int32_t* P = c.ws.P + size_t(b) * (L + 1);
