@@ -21,6 +21,7 @@ namespace {
 constexpr uint32_t kInf = 1u << 30;
 constexpr int kT = 8;  // stage-block size of the fill
 constexpr int kCH = 4;  // 64-column chunks of m per gemm work-group
+constexpr int kRowWG = 256;  // threads (columns of m) per row_kernel work-group
 std::atomic<int> g_last_hip_error{0};
 
 inline bool hip_ok(hipError_t e) {
@@ -419,7 +420,7 @@ __global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
 // trip count is static: all operand addresses are known up front, the loads are issued
 // together and the kernel pays the memory latency once instead of once per split.
 template <int T, int R, int DC>
-__global__ void __launch_bounds__(256) row_kernel(Ctx c, int D) {
+__global__ void __launch_bounds__(kRowWG) row_kernel(Ctx c, int D) {
     constexpr int CF = (DC == 0) ? R : 0;                              // first column with j >= i
     constexpr int NQ = (DC == 0) ? 0 : (DC == 1 ? T - R : T - 1 - R);  // near-i splits (D = 1: and q = jb)
     constexpr int NQA = NQ > 0 ? NQ : 1;
@@ -427,7 +428,7 @@ __global__ void __launch_bounds__(256) row_kernel(Ctx c, int D) {
     const int L = c.L, pitch = c.pitch;
     const int i = I * T + R;
     if (i >= L) return;
-    const uint32_t m = blockIdx.x * 256 + threadIdx.x;
+    const uint32_t m = blockIdx.x * kRowWG + threadIdx.x;
     if (m >= uint32_t(pitch)) return;
     const uint32_t moff = m * 4;
     const size_t chain = size_t(b) * c.rows * pitch;
@@ -732,7 +733,7 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     }
     constexpr int T = kT;
     const int nblk = (L + T - 1) / T;
-    const int gx_gemm = (pitch / 64 + kCH - 1) / kCH, gx_row = (pitch + 255) / 256;
+    const int gx_gemm = (pitch / 64 + kCH - 1) / kCH, gx_row = (pitch + kRowWG - 1) / kRowWG;
 
     // Two streams.  Chains are independent, so from D = 2 on the batch is split in two halves
     // that run the same launch sequence on two streams: the many short row launches of one half
@@ -756,7 +757,7 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
         const Ctx ctx{L, M, pitch, rows, b0, ws, cost, arg};
         const auto& rowfn = D == 0 ? kRow0 : (D == 1 ? kRow1 : kRow2);
         for (int r = T - 1; r >= 0; --r) {
-            hipLaunchKernelGGL(rowfn[r], dim3(gx_row, nblk - D, nb), dim3(256), 0, s, ctx, D);
+            hipLaunchKernelGGL(rowfn[r], dim3(gx_row, nblk - D, nb), dim3(kRowWG), 0, s, ctx, D);
             CKPT_AFTER_LAUNCH(CKPT_K_ROW);
         }
         return CKPT_OK;
@@ -784,7 +785,7 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
         for (int r = T - 1; r >= 0; --r) {
             for (int g = 0; g < groups; ++g) {
                 const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
-                hipLaunchKernelGGL(rowfn[r], dim3(gx_row, nblk - D, first[g + 1] - first[g]), dim3(256), 0, gs[g],
+                hipLaunchKernelGGL(rowfn[r], dim3(gx_row, nblk - D, first[g + 1] - first[g]), dim3(kRowWG), 0, gs[g],
                                    ctx, D);
                 CKPT_AFTER_LAUNCH(CKPT_K_ROW);
             }
