@@ -53,6 +53,30 @@ def gemm_work(L, M, B, T=8):
     return evals * (M + 1) * B, cells * (M + 1) * B
 
 
+def row_bytes(L, M, B, T=8):
+    """Algorithmic bytes of all row_kernel launches of a step (nominal: waves that the frontier
+    test skips still count).  Per lane and row r of a tile: 9 loads per near-i split (left + 8
+    right), 5 bytes per cell of gemm partial (D >= 2), one load per near-j candidate, one C_all
+    operand per cell with j > i, and 5 bytes stored per cell."""
+    nblk = (L + T - 1) // T
+    total = 0
+    for D in range(nblk):
+        for I in range(nblk - D):
+            J = I + D
+            for r in range(T):
+                i = I * T + r
+                if i >= L:
+                    continue
+                cols = [j for j in range(J * T, min(L, J * T + T)) if j >= i]
+                near_i = 0 if D == 0 else ((T - r) if D == 1 else (T - 1 - r))
+                loads = near_i * (1 + T)                                   # clamped columns are loaded too
+                loads += sum(1 for j in cols for q in range(max(i + 1, J * T + 1), j + 1))   # near-j
+                loads += sum(1 for j in cols if j > i)                     # C_all
+                nbytes = 4 * loads + (5 * T if D >= 2 else 0) + 5 * len(cols)
+                total += nbytes
+    return total * (M + 1) * B
+
+
 def measured_traffic(workload, kernel):
     """HBM bytes per launch of `kernel` from the committed rocprofv3 counter summary of this
     workload (profiles/<kernel>_<workload>_pmc.txt, line 'traffic_bytes_per_launch: N'), or None."""
@@ -207,21 +231,27 @@ def main():
     batch = r["batch"]
     evals_per_s = r["evals"] / (r["ms"] * 1e-3)
     kinds = r["kinds"]
-    dom = "gemm_kernel"
-    dom_evals, dom_cells = gemm_work(batch.L, batch.M, batch.B)
+    dom = max(("gemm_kernel", "row_kernel"), key=lambda k: kinds[k]["ms_per_step"])
+    gemm_evals, gemm_cells = gemm_work(batch.L, batch.M, batch.B)
     dom_ms = kinds[dom]["ms_per_step"]
     launches = max(1, kinds[dom]["launches_per_step"])
     per_launch_s = dom_ms * 1e-3 / launches
-    alg_bytes = (GEMM_BYTES_PER_EVAL * dom_evals + GEMM_BYTES_PER_CELL * dom_cells) / launches
-    alg_ops = GEMM_OPS_PER_EVAL * dom_evals / launches
+    if dom == "gemm_kernel":
+        alg_bytes = (GEMM_BYTES_PER_EVAL * gemm_evals + GEMM_BYTES_PER_CELL * gemm_cells) / launches
+        dom_evals, ops_per_eval = gemm_evals, GEMM_OPS_PER_EVAL
+        alu_unit = "Tlane-op/s (float64 add + min per candidate)"
+    else:
+        alg_bytes = row_bytes(batch.L, batch.M, batch.B) / launches
+        dom_evals, ops_per_eval = r["evals"] - gemm_evals, 4     # add, compare, two selects per candidate
+        alu_unit = "Tlane-op/s (32-bit add, compare, two selects per candidate)"
+    alg_ops = ops_per_eval * dom_evals / launches
     roofline = {"bound": "hbm", "kernel": dom, "achieved": alg_bytes / per_launch_s / 1e9, "peak": PEAK_HBM / 1e9,
                 "unit": "GB/s", "frac": alg_bytes / per_launch_s / PEAK_HBM,
                 "traffic": measured_traffic(batch.name, dom),
                 "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": per_launch_s * 1e3,
                 "launches_per_step": launches, "evals_in_kernel_per_step": dom_evals,
                 "alu": {"achieved": alg_ops / per_launch_s / 1e12, "peak": PEAK_VALU_OPS / 1e12,
-                        "unit": "Tlane-op/s (float64 add + min per candidate)",
-                        "frac": alg_ops / per_launch_s / PEAK_VALU_OPS}}
+                        "unit": alu_unit, "frac": alg_ops / per_launch_s / PEAK_VALU_OPS}}
     out = {
         "metric": "min-plus candidate evaluations per second (whole batch, tables resident in HBM)",
         "value": evals_per_s, "unit": "evals/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
