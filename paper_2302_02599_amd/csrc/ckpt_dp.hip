@@ -741,7 +741,9 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     // launches.  Before that, the frontier (a few busy CUs for a long time) runs on the second
     // stream next to the D = 0 and D = 1 rows of the whole batch, which do not need it.  The
     // second stream is forked from and joined back into the caller's stream with events.
-    Side* side = (!prof && B >= 2 && nblk >= 3) ? side_streams() : nullptr;
+    // Small problems are bound by launch latency, where a second stream only adds launches.
+    const bool split = !prof && B >= 2 && nblk >= 3 && size_t(B) * nblk * pitch >= (size_t(1) << 19);
+    Side* side = split ? side_streams() : nullptr;
     std::unique_lock<std::mutex> lock;
     if (side) lock = std::unique_lock<std::mutex>(side->busy);  // one fork/join at a time per device
     hipStream_t s2 = side ? side->stream : st;
