@@ -266,12 +266,14 @@ __device__ __forceinline__ uint32_t ld32(rsrc_t tab, uint32_t elem, uint32_t off
 
 // Middle splits of every tile of block diagonal D >= 2.
 // One wave owns the 8x8 tile of cells for 64 consecutive m; lane = m.  Each loaded operand
-// row is used by 8 cells (1 byte of table traffic per candidate instead of 8).
+// row is used by 8 cells (1 byte of table traffic per candidate instead of 8).  The CH waves of
+// a work-group take adjacent chunks of m of the same tile: they share one work list, and the
+// cache lines that a shifted operand read straddles are fetched once for two waves.
 // Candidates are compared as float64 keys  cost + (q+1)/256 : one add and one min per
 // candidate give the minimum cost and, among equal costs, the smallest candidate number
 // (all values are integers below 2^34 scaled by 2^-8, exact in float64).
 // Splits whose operands are infeasible for the whole chunk (frontier test) are dropped
-// from the wave's work list before the pipeline starts.
+// from the work list before the pipeline starts.
 // Output: cost[] <- unsaturated partial minimum (0xffffffff if none), arg[] <- its number.
 template <int NB, int UNR, int CH>
 __global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
@@ -297,8 +299,8 @@ __global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
 #pragma unroll
     for (int cc = 0; cc < 8; ++cc) jcol[cc] = min(j0 + cc, L - 1);
 
-    // Work list of this wave: the splits q for which some cell of the tile can have both
-    // operands feasible somewhere in this chunk.  Per-split constants (shift, key offset)
+    // Work list of the work-group: the splits q for which some cell of the tile can have both
+    // operands feasible somewhere in its CH chunks.  Per-split constants (shift, key offset)
     // travel with the list through LDS, so the pipeline never waits on scalar memory.
     __shared__ double s_kq[CKPT_MAX_L + 2];
     __shared__ int32_t s_sh[CKPT_MAX_L + 2];

@@ -49,6 +49,20 @@ def test_ragged_shapes(amd, oracle_mod, L, M, B, seed, ovh, wd, zero):
     assert_tables_equal(oracle_mod, batch, amd.solve(batch), nthreads=4)
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_shapes(amd, oracle_mod, seed):
+    """Seeded sweep over chain lengths, budgets, batch sizes and optional arrays."""
+    rng = np.random.default_rng(9000 + seed)
+    L = int(rng.integers(1, 90))
+    M = int(rng.integers(0, 700))
+    B = int(rng.integers(1, 6))
+    batch = random_chain_batch(L, M, B, 500 + seed, size_hi=int(rng.integers(1, 12)),
+                               time_hi=int(rng.integers(2, 3000)), overheads=bool(rng.integers(2)),
+                               own_wdelta=bool(rng.integers(2)), zero_sizes=bool(rng.integers(2)))
+    print(f"case {batch.name} size_hi etc. seed {seed}", flush=True)
+    assert_tables_equal(oracle_mod, batch, amd.solve(batch), nthreads=4)
+
+
 def test_everything_infeasible(amd, oracle_mod):
     batch = random_chain_batch(12, 3, 2, 21, size_hi=9)
     batch.wa += 5
