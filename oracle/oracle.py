@@ -6,7 +6,8 @@ and this module imports nothing from the GPU package.
 
 solve_chain / solve_batch evaluate the recurrence of the paper's Theorem
 (Section "Activation Checkpoint Solver / Modeling"); reconstruct() walks the
-recorded choices into the operation sequence of Table 1.
+recorded choices into the operation sequence of Table 1; simulate() executes such
+a sequence under the memory model of Table 1.
 """
 from __future__ import annotations
 
@@ -122,6 +123,74 @@ def reconstruct(choice, wa, wabar, s, t, m):
     ops += reconstruct(choice, wa, wabar, k, t, m - int(wa[k - 1]))
     ops += reconstruct(choice, wa, wabar, s, k - 1, m)
     return ops
+
+
+def simulate(ops, L, uf, ub, wa, wabar, wdelta=None, of=None, ob=None):
+    """Run an operation list over the whole chain 1..L and return (time, peak memory).
+
+    The operations are those of Table 1 ("List of Operations"): F_all^j and F_ck^j read
+    a^{j-1} (plain, or inside abar^{j-1}), keep it and add abar^j resp. a^j; F_null^j reads a
+    plain a^{j-1}, adds a^j and drops a^{j-1}; B^j reads delta^j, abar^j and a^{j-1} (plain or
+    inside abar^{j-1}), adds delta^{j-1} and drops delta^j, abar^j and a plain a^{j-1}.  An
+    operation takes u_f^j resp. u_b^j and needs o_f^j resp. o_b^j on top of what is resident.
+
+    Memory is counted the way the Theorem's thresholds count it: the chain input a^0 is free,
+    delta^L is resident from the start, a forward operation needs room for its output while it
+    runs, B^j does not count its output delta^{j-1} while it runs.
+    Raises ValueError for a list that cannot be executed (a missing operand, a tensor computed
+    while it is still resident, an unknown operation) or that ends without delta^0.
+    """
+    wd = wa if wdelta is None else wdelta
+    of = [0] * L if of is None else of
+    ob = [0] * L if ob is None else ob
+    plain = [False] * (L + 1)   # a^j resident on its own
+    full = [False] * (L + 1)    # abar^j resident (contains a^j)
+    grad = [False] * (L + 1)    # delta^j resident
+    plain[0] = True
+    grad[L] = True
+
+    def resident():
+        total = 0
+        for j in range(L + 1):
+            if plain[j] and j > 0:
+                total += int(wa[j])
+            if full[j]:
+                total += int(wabar[j - 1])
+            if grad[j]:
+                total += int(wd[j])
+        return total
+
+    time = peak = 0
+    for kind, j in ops:
+        kind, j = int(kind), int(j)
+        if not 1 <= j <= L:
+            raise ValueError(f"stage {j} outside the chain")
+        if kind in (F_ALL, F_CK, F_NULL):
+            if not (plain[j - 1] or full[j - 1]):
+                raise ValueError(f"forward of stage {j} without a^{j - 1}")
+            if kind == F_NULL and not plain[j - 1]:
+                raise ValueError(f"F_null^{j} needs a plain a^{j - 1}")
+            made = full if kind == F_ALL else plain
+            if made[j]:
+                raise ValueError(f"output of stage {j} is already resident")
+            size = int(wabar[j - 1]) if kind == F_ALL else int(wa[j])
+            peak = max(peak, resident() + size + int(of[j - 1]))
+            made[j] = True
+            if kind == F_NULL:
+                plain[j - 1] = False
+            time += int(uf[j - 1])
+        elif kind == BWD:
+            if not (grad[j] and full[j] and (plain[j - 1] or full[j - 1])):
+                raise ValueError(f"B^{j} without its operands")
+            peak = max(peak, resident() + int(ob[j - 1]))
+            grad[j] = full[j] = plain[j - 1] = False
+            grad[j - 1] = True
+            time += int(ub[j - 1])
+        else:
+            raise ValueError(f"unknown operation {kind}")
+    if not grad[0]:
+        raise ValueError("the list ends without delta^0")
+    return time, peak
 
 
 def min_feasible_memory(L, wa, wabar, wdelta=None, of=None, ob=None):
