@@ -156,10 +156,18 @@ def time_planner_steps(amd, idx, dev, reps=20):
     by_wa, by_wabar = wa.to(torch.int64) * 1000, wabar.to(torch.int64) * 1000
     budget_bytes = torch.full((B,), 1000 * M, dtype=torch.int64, device=dev)
     o_wa, o_wabar = torch.empty_like(wa), torch.empty_like(wabar)
+    uf, ub = torch.from_numpy(batch.uf).to(dev), torch.from_numpy(batch.ub).to(dev)
+    extra = {k: None if getattr(batch, k) is None else torch.from_numpy(getattr(batch, k)).to(dev)
+             for k in ("wdelta", "of", "ob")}
+    sim_time = torch.zeros(B, dtype=torch.int64, device=dev)
+    sim_peak = torch.zeros(B, dtype=torch.int64, device=dev)
+    sim_status = torch.zeros(B, dtype=torch.int32, device=dev)
     steps = {
         "ckpt_select_plan": lambda: amd.ckpt_select_plan(sol.cost, L, M, B, budgets, out),
         "ckpt_schedule_batched": lambda: amd.ckpt_schedule_batched(sol.arg, wa, wabar, L, M, B, budgets, ops, cap,
                                                                    n_ops, ws),
+        "ckpt_simulate_batched": lambda: amd.ckpt_simulate_batched(uf, ub, wa, wabar, L, B, ops, cap, n_ops, sim_time,
+                                                                   sim_peak, sim_status, **extra),
         "ckpt_discretize": lambda: amd.ckpt_discretize(by_wa, by_wabar, budget_bytes, L, M, B, o_wa, o_wabar),
     }
     res = {}
@@ -172,6 +180,8 @@ def time_planner_steps(amd, idx, dev, reps=20):
         torch.cuda.synchronize()
         res[name] = (time.perf_counter() - t0) / reps * 1e6
     assert (o_wa == wa).all() and int(out[0]) >= 0 and int(n_ops.min()) > 0
+    root = amd.ckpt_row_index(L, 1, L)
+    assert (sim_status == 0).all() and (sim_time == sol.cost[:, root, M]).all() and int(sim_peak.max()) <= M
     return {"workload": batch.name, "us_per_call": res}
 
 

@@ -210,6 +210,30 @@ int ckpt_schedule_batched(const uint8_t* arg, const int32_t* wa, const int32_t* 
 size_t ckpt_schedule_workspace_bytes(int L, int B);
 
 /*
+ * Self-check of operation lists on the device: the list of every chain is executed over
+ * stages 1..L under the memory model of Table 1 ("List of Operations") -- F_all^j and F_ck^j
+ * read a^{j-1} (on its own or inside abar^{j-1}), keep it and add abar^j resp. a^j; F_null^j
+ * reads a^{j-1} on its own, adds a^j and drops a^{j-1}; B^j reads delta^j, abar^j and a^{j-1},
+ * adds delta^{j-1} and drops delta^j, abar^j and an a^{j-1} held on its own -- counted the way
+ * the Theorem's thresholds count: a^0 is free, delta^L is resident from the start, a forward
+ * operation needs room for its output and o_f^j while it runs, B^j needs o_b^j and does not
+ * count its output while it runs.  A list realises cell (1, L, m) of the cost table exactly
+ * when time_out equals the cell's cost and peak_out <= m.
+ *   chains     host struct of DEVICE pointers, as for ckpt_solve_batched (values >= 0)
+ *   ops, ops_cap, n_ops   DEVICE, as written by ckpt_schedule_batched
+ *   time_out   DEVICE int64 [B]: sum of u_f / u_b over the list, -1 unless status is CKPT_OK
+ *   peak_out   DEVICE int64 [B]: largest memory need over the list, -1 unless status is CKPT_OK
+ *   status     DEVICE int32 [B]: CKPT_OK; CKPT_E_CORRUPT for a list that cannot be executed (an
+ *              operand that is not resident, a tensor computed while it is resident, an unknown
+ *              operation or stage) or that ends without delta^0; CKPT_E_ARG if n_ops[b] >
+ *              ops_cap; n_ops[b] itself if that is negative (the chain is skipped)
+ * Returns CKPT_OK, CKPT_E_ARG, CKPT_E_LIMIT or CKPT_E_HIP.
+ */
+int ckpt_simulate_batched(const ckpt_chains_t* chains, int L, int B, const ckpt_op_t* ops, int ops_cap,
+                          const int32_t* n_ops, void* stream, int64_t* time_out, int64_t* peak_out,
+                          int32_t* status);
+
+/*
  * Network linearisation on the host (Sections "Linearization", "Common Node" and the
  * algorithm of "Full Set of Linearization Rules"): cuts a computation DAG into the node
  * groups that become the stages of a chain.

@@ -46,6 +46,9 @@ def load_library():
     if not os.path.exists(_LIB_PATH):
         raise ImportError(f"{_LIB_PATH} is missing: run `python paper_2302_02599_amd/build.py` "
                           "(or __graft_entry__.build()) first; there is no fallback path")
+    # PyTorch ships its own HIP runtime and supplies the device memory and streams used here:
+    # it has to be loaded first, so that this library binds to that runtime and not to a second one.
+    import torch  # noqa: F401
     lib = ctypes.CDLL(_LIB_PATH)
     sz, i, vp = ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p
     lib.ckpt_row_pitch.restype, lib.ckpt_row_pitch.argtypes = sz, [i]
@@ -69,6 +72,8 @@ def load_library():
     lib.ckpt_schedule_batched.restype = i
     lib.ckpt_schedule_batched.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp, i, vp, vp]
     lib.ckpt_schedule_workspace_bytes.restype, lib.ckpt_schedule_workspace_bytes.argtypes = sz, [i, i]
+    lib.ckpt_simulate_batched.restype = i
+    lib.ckpt_simulate_batched.argtypes = [ctypes.POINTER(_Chains), i, i, vp, i, vp, vp, vp, vp, vp]
     lib.ckpt_linearize.restype = i
     lib.ckpt_linearize.argtypes = [i, vp, vp, vp, vp, vp]
     lib.ckpt_last_hip_error.restype, lib.ckpt_last_hip_error.argtypes = i, []
@@ -238,6 +243,23 @@ def ckpt_schedule_batched(arg, wa, wabar, L, M, B, m_budget, ops, ops_cap, n_ops
         _dev(workspace, "workspace", torch.uint8, ckpt_schedule_workspace_bytes(L, B)))
     if rc != 0:
         raise CkptError(rc, "ckpt_schedule_batched")
+
+
+def ckpt_simulate_batched(uf, ub, wa, wabar, L, B, ops, ops_cap, n_ops, time_out, peak_out, status, *, wdelta=None,
+                          of=None, ob=None, stream=None) -> None:
+    """Device execution of every chain's operation list under the memory model of Table 1:
+    time_out / peak_out int64 [B], status int32 [B]."""
+    import torch
+    i32 = torch.int32
+    chains = _Chains(_dev(uf, "uf", i32, B * L), _dev(ub, "ub", i32, B * L), _dev(wa, "wa", i32, B * (L + 1)),
+                     _dev(wabar, "wabar", i32, B * L), _dev(wdelta, "wdelta", i32, B * (L + 1)),
+                     _dev(of, "of", i32, B * L), _dev(ob, "ob", i32, B * L))
+    rc = load_library().ckpt_simulate_batched(
+        ctypes.byref(chains), L, B, _dev(ops, "ops", torch.uint8, B * ops_cap * 2), ops_cap,
+        _dev(n_ops, "n_ops", i32, B), _stream(stream), _dev(time_out, "time_out", torch.int64, B),
+        _dev(peak_out, "peak_out", torch.int64, B), _dev(status, "status", i32, B))
+    if rc != 0:
+        raise CkptError(rc, "ckpt_simulate_batched")
 
 
 def ckpt_linearize(children, flags):

@@ -657,6 +657,88 @@ __global__ void __launch_bounds__(64) schedule_kernel(const uint8_t* __restrict_
     n_ops[b] = err ? err : n;
 }
 
+// Self-check of operation lists: one wave per chain executes its list under the memory model
+// of Table 1 ("List of Operations").  The lanes stage the chain's arrays and the list through
+// LDS; lane 0 carries the state: per stage j one byte with bit 0 = a^j resident on its own,
+// bit 1 = abar^j resident, bit 2 = delta^j resident, and the running sum of resident sizes.
+constexpr int kSimChunk = 256;  // operations staged per pass, a multiple of the wave size
+
+__global__ void __launch_bounds__(64) simulate_kernel(ckpt_chains_t ch, int L, const ckpt_op_t* __restrict__ ops,
+                                                       int cap, const int32_t* __restrict__ n_ops,
+                                                       long long* __restrict__ time_out,
+                                                       long long* __restrict__ peak_out, int32_t* __restrict__ status) {
+    __shared__ int32_t s_uf[CKPT_MAX_L], s_ub[CKPT_MAX_L], s_wab[CKPT_MAX_L], s_of[CKPT_MAX_L], s_ob[CKPT_MAX_L];
+    __shared__ int32_t s_wa[CKPT_MAX_L + 1], s_wd[CKPT_MAX_L + 1];
+    __shared__ uint8_t s_state[CKPT_MAX_L + 2];
+    __shared__ ckpt_op_t s_ops[kSimChunk];
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int n = n_ops[b];
+    if (n < 0 || n > cap) {  // uniform over the wave
+        if (lane == 0) {
+            status[b] = n < 0 ? n : CKPT_E_ARG;
+            time_out[b] = peak_out[b] = -1;
+        }
+        return;
+    }
+    const int32_t* wd = ch.wdelta ? ch.wdelta : ch.wa;
+    for (int k = lane; k < L; k += 64) {
+        s_uf[k] = ch.uf[size_t(b) * L + k];
+        s_ub[k] = ch.ub[size_t(b) * L + k];
+        s_wab[k] = ch.wabar[size_t(b) * L + k];
+        s_of[k] = ch.of ? ch.of[size_t(b) * L + k] : 0;
+        s_ob[k] = ch.ob ? ch.ob[size_t(b) * L + k] : 0;
+    }
+    for (int k = lane; k <= L; k += 64) {
+        s_wa[k] = k ? ch.wa[size_t(b) * (L + 1) + k] : 0;  // the chain input a^0 is not counted
+        s_wd[k] = wd[size_t(b) * (L + 1) + k];
+        s_state[k] = k == 0 ? 1 : k == L ? 4 : 0;  // a^0 and delta^L are there from the start
+    }
+    __syncthreads();
+    const ckpt_op_t* list = ops + size_t(b) * cap;
+    long long time = 0, peak = 0, resident = s_wd[L];
+    bool bad = false;
+    for (int base = 0; base < n; base += kSimChunk) {  // n is uniform over the wave
+        if (base) __syncthreads();  // lane 0 is done with the previous part of the list
+        for (int k = lane; k < kSimChunk && base + k < n; k += 64) s_ops[k] = list[base + k];
+        __syncthreads();
+        if (lane != 0 || bad) continue;
+        const int end = min(kSimChunk, n - base);
+        for (int k = 0; k < end; ++k) {
+            const int kind = s_ops[k].kind, j = s_ops[k].stage;
+            if (j < 1 || j > L || kind > CKPT_OP_B) { bad = true; break; }
+            const int in = s_state[j - 1], self = s_state[j];
+            if (kind == CKPT_OP_B) {  // needs delta^j, abar^j and a^{j-1}; its output is not counted while it runs
+                if (!(self & 4) || !(self & 2) || !(in & 3)) { bad = true; break; }
+                peak = max(peak, resident + s_ob[j - 1]);
+                resident -= (long long)s_wd[j] + s_wab[j - 1];
+                if (in & 1) resident -= s_wa[j - 1];
+                if (!(in & 4)) resident += s_wd[j - 1];
+                s_state[j] = uint8_t(self & 1);
+                s_state[j - 1] = uint8_t((in & 2) | 4);
+                time += s_ub[j - 1];
+            } else {  // a forward operation needs room for its output; F_null drops its input
+                const int bit = kind == CKPT_OP_F_ALL ? 2 : 1;
+                if (!(in & 3) || (kind == CKPT_OP_F_NULL && !(in & 1)) || (self & bit)) { bad = true; break; }
+                const long long size = kind == CKPT_OP_F_ALL ? s_wab[j - 1] : s_wa[j];
+                peak = max(peak, resident + size + s_of[j - 1]);
+                resident += size;
+                s_state[j] = uint8_t(self | bit);
+                if (kind == CKPT_OP_F_NULL) {
+                    resident -= s_wa[j - 1];
+                    s_state[j - 1] = uint8_t(in & ~1);
+                }
+                time += s_uf[j - 1];
+            }
+        }
+    }
+    if (lane == 0) {
+        if (!bad && !(s_state[0] & 4)) bad = true;  // the list must end with delta^0
+        status[b] = bad ? CKPT_E_CORRUPT : CKPT_OK;
+        time_out[b] = bad ? -1 : time;
+        peak_out[b] = bad ? -1 : peak;
+    }
+}
+
 int check_dims(int L, int M, int B) {
     if (L < 1 || M < 0 || B < 1) return CKPT_E_ARG;
     if (L > CKPT_MAX_L) return CKPT_E_LIMIT;
@@ -918,6 +1000,19 @@ int ckpt_schedule_batched(const uint8_t* arg, const int32_t* wa, const int32_t* 
     hipLaunchKernelGGL(schedule_kernel, dim3((B + 63) / 64), dim3(64), 0, static_cast<hipStream_t>(stream), arg, wa,
                        wabar, L, M, int(ckpt_row_pitch(M)), int(ckpt_table_rows(L)), B, m_budget, ops, ops_cap,
                        n_ops, static_cast<int4*>(workspace));
+    return hip_ok(hipGetLastError()) ? CKPT_OK : CKPT_E_HIP;
+}
+
+int ckpt_simulate_batched(const ckpt_chains_t* chains, int L, int B, const ckpt_op_t* ops, int ops_cap,
+                          const int32_t* n_ops, void* stream, int64_t* time_out, int64_t* peak_out,
+                          int32_t* status) {
+    if (!chains || !chains->uf || !chains->ub || !chains->wa || !chains->wabar || !ops || !n_ops || !time_out ||
+        !peak_out || !status || ops_cap < 0 || L < 1 || B < 1)
+        return CKPT_E_ARG;
+    if (L > CKPT_MAX_L) return CKPT_E_LIMIT;
+    hipLaunchKernelGGL(simulate_kernel, dim3(B), dim3(64), 0, static_cast<hipStream_t>(stream), *chains, L, ops,
+                       ops_cap, n_ops, reinterpret_cast<long long*>(time_out), reinterpret_cast<long long*>(peak_out),
+                       status);
     return hip_ok(hipGetLastError()) ? CKPT_OK : CKPT_E_HIP;
 }
 

@@ -150,3 +150,116 @@ def test_schedule_batched_small_capacity_and_corrupt_table(amd, solved):
     amd.ckpt_schedule_batched(broken, wa, wabar, L, M, B, budgets, ops, cap, n_ops, ws)
     got = n_ops.cpu().tolist()
     assert got[3] == -7 and all(v > 0 for k, v in enumerate(got) if k != 3)
+
+
+def _simulate_on_device(amd, batch, ops, cap, n_ops):
+    import torch
+    up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
+    B = batch.B
+    time = torch.full((B,), -9, dtype=torch.int64, device="cuda")
+    peak = torch.full((B,), -9, dtype=torch.int64, device="cuda")
+    status = torch.full((B,), -9, dtype=torch.int32, device="cuda")
+    amd.ckpt_simulate_batched(up(batch.uf), up(batch.ub), up(batch.wa), up(batch.wabar), batch.L, B, ops, cap, n_ops,
+                              time, peak, status, wdelta=up(batch.wdelta), of=up(batch.of), ob=up(batch.ob))
+    return time.cpu().tolist(), peak.cpu().tolist(), status.cpu().tolist()
+
+
+def _oracle_simulation(oracle_mod, batch, b, ops):
+    try:
+        return oracle_mod.simulate(ops, batch.L, *batch.chain(b)) + (0,)
+    except ValueError:
+        return (-1, -1, -7)
+
+
+def _check_walk_then_simulate(amd, oracle_mod, batch, sol, tables, budgets, name):
+    import torch
+    L, M, B = batch.L, batch.M, batch.B
+    cap = L * (L + 1) // 2 + L
+    ws = torch.empty(amd.ckpt_schedule_workspace_bytes(L, B), dtype=torch.uint8, device="cuda")
+    ops = torch.zeros((B, cap, 2), dtype=torch.uint8, device="cuda")
+    n_ops = torch.zeros(B, dtype=torch.int32, device="cuda")
+    amd.ckpt_schedule_batched(sol.arg, torch.from_numpy(batch.wa).cuda(), torch.from_numpy(batch.wabar).cuda(), L, M, B,
+                              torch.tensor(budgets, dtype=torch.int32, device="cuda"), ops, cap, n_ops, ws)
+    time, peak, status = _simulate_on_device(amd, batch, ops, cap, n_ops)
+    n_h = n_ops.cpu().tolist()
+    longest = 0
+    for b in range(B):
+        if n_h[b] < 0:
+            assert (time[b], peak[b], status[b]) == (-1, -1, n_h[b]), (name, b)
+            continue
+        m = min(budgets[b], M)
+        want_ops = oracle_mod.reconstruct(tables[b][1], batch.wa[b], batch.wabar[b], 1, L, m)
+        want = _oracle_simulation(oracle_mod, batch, b, want_ops)
+        assert (time[b], peak[b], status[b]) == want, (name, b)
+        assert status[b] == 0 and time[b] == tables[b][0][0, L - 1, m] and peak[b] <= m, (name, b)
+        longest = max(longest, n_h[b])
+    return longest
+
+
+def test_simulate_batched_confirms_the_walked_schedules(amd, oracle_mod, solved):
+    batch, sol, tables = solved
+    for name, budgets in _budget_sets(batch, tables, oracle_mod):
+        _check_walk_then_simulate(amd, oracle_mod, batch, sol, tables, budgets, name)
+
+
+def test_simulate_batched_with_overheads_own_gradient_sizes_and_long_lists(amd, oracle_mod):
+    from workloads.chains import random_chain_batch
+    batch = random_chain_batch(70, 700, 3, 41, size_hi=9, time_hi=900, overheads=True, own_wdelta=True)
+    sol = amd.solve(batch)
+    tables = oracle_mod.solve_batch(batch, nthreads=8)
+    L, M = batch.L, batch.M
+    first = [int(np.argmax(t[0][0, L - 1] < oracle_mod.INF)) for t in tables]
+    assert all(tables[b][0][0, L - 1, first[b]] < oracle_mod.INF for b in range(batch.B))
+    longest = 0
+    for name, budgets in (("tightest", first), ("roomy", [M] * batch.B), ("between", [(f + M) // 3 for f in first])):
+        longest = max(longest, _check_walk_then_simulate(amd, oracle_mod, batch, sol, tables, budgets, name))
+    assert longest > 2 * 256  # the list is staged through on-chip memory in several parts
+
+
+def test_simulate_batched_edited_lists(amd, oracle_mod):
+    """Persistent schedules with random edits, most of them no longer executable, plus unknown
+    operations and stages: the status, and the figures of those that still run, match the oracle."""
+    import torch
+    import persistent_bruteforce as bf
+    from workloads.chains import random_chain_batch
+    L, B, cap = 4, 256, 16
+    batch = random_chain_batch(L, 8, B, 78, size_hi=6, time_hi=40, overheads=True, own_wdelta=True)
+    rng = np.random.default_rng(6)
+    base = [bf.flatten(t) for t in bf.trees(1, L)]
+    lists = []
+    for b in range(B):
+        ops = list(base[int(rng.integers(len(base)))])
+        for _ in range(int(rng.integers(0, 3))):
+            i = int(rng.integers(len(ops)))
+            edit = int(rng.integers(6))
+            if edit == 0 and len(ops) > 1:
+                del ops[i]
+            elif edit == 1:
+                ops.insert(i, ops[i])
+            elif edit == 2:
+                ops.insert(int(rng.integers(len(ops))), ops.pop(i))
+            elif edit == 3:
+                ops[i] = (int(rng.integers(0, 6)), ops[i][1])
+            elif edit == 4:
+                ops[i] = (ops[i][0], int(rng.integers(0, L + 3)))
+            else:
+                ops[i] = (ops[i][0], 255)
+        lists.append(ops[:cap])
+    lists[0] = []            # an empty list ends without the gradient of the input
+    ops_h = np.zeros((B, cap, 2), np.uint8)
+    for b, ops in enumerate(lists):
+        ops_h[b, :len(ops)] = np.array(ops, np.uint8).reshape(-1, 2)
+    n_h = np.array([len(o) for o in lists], np.int32)
+    n_h[1], n_h[2] = cap + 1, -3          # too long for the buffer; a chain the walk gave up on
+    time, peak, status = _simulate_on_device(amd, batch, torch.from_numpy(ops_h).cuda(), cap, torch.from_numpy(n_h).cuda())
+    kinds = set()
+    for b in range(B):
+        if b == 1:
+            want = (-1, -1, -1)
+        elif b == 2:
+            want = (-1, -1, -3)
+        else:
+            want = _oracle_simulation(oracle_mod, batch, b, lists[b])
+        assert (time[b], peak[b], status[b]) == want, (b, lists[b])
+        kinds.add(status[b])
+    assert kinds == {0, -1, -3, -7}
