@@ -185,15 +185,42 @@ def time_planner_steps(amd, idx, dev, reps=20):
     return {"workload": batch.name, "us_per_call": res}
 
 
-def cpu_baseline(idx, budget_s=25.0):
+def time_d2h(amd, idx, dev):
+    """Copy of the finished tables to pinned host memory; reported beside the solve, never part of it."""
+    import torch
+    from workloads import make_config
+    sol = amd.solve(make_config(idx), device=str(dev))
+    host = [torch.empty(t.shape, dtype=t.dtype, pin_memory=True) for t in (sol.cost, sol.arg)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for h, t in zip(host, (sol.cost, sol.arg)):
+        h.copy_(t, non_blocking=True)
+    torch.cuda.synchronize()
+    el = time.perf_counter() - t0
+    nbytes = sum(h.numel() * h.element_size() for h in host)
+    return {"ms": el * 1e3, "bytes": nbytes, "GB/s": nbytes / el / 1e9}
+
+
+def cpu_model():
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
+def cpu_baseline(idx, budget_s=20.0):
     """The oracle as it stands, on the host cores, on a bounded sample of the workload:
-    whole chains of the batch, one after the other, until about budget_s seconds are spent."""
+    whole chains of the batch, one after the other, until about budget_s seconds are spent;
+    then one more chain on a single thread."""
     from oracle import oracle
     from workloads import make_config
     batch = make_config(idx)
     threads = oracle.max_threads()
-    _, evals_chain = counts(batch.L, batch.M, 1)
-    cells_chain, _ = counts(batch.L, batch.M, 1)
+    cells_chain, evals_chain = counts(batch.L, batch.M, 1)
     done, t0 = 0, time.perf_counter()
     while done < batch.B:
         oracle.solve_chain(batch.L, batch.M, *batch.chain(done), nthreads=threads)
@@ -202,8 +229,13 @@ def cpu_baseline(idx, budget_s=25.0):
         if el + el / done > budget_s:
             break
     el = time.perf_counter() - t0
+    t1 = time.perf_counter()
+    oracle.solve_chain(batch.L, batch.M, *batch.chain(0), nthreads=1)
+    el1 = time.perf_counter() - t1
     return {"value": evals_chain * done / el, "unit": "evals/s", "cores": threads, "kind": "oracle",
             "cells_per_s": cells_chain * done / el,
+            "single_thread": {"value": evals_chain / el1, "unit": "evals/s", "sample": f"chain 0, {el1:.1f} s"},
+            "cpu": cpu_model(), "host_cpus": os.cpu_count(),
             "sample": f"chains 0..{done - 1} of {batch.B} of {batch.name}, full tables, {el:.1f} s, "
                       f"OpenMP over the rows of one segment length"}
 
@@ -283,6 +315,7 @@ def main():
                                        "cells_per_s": o["cells"] / (o["ms"] * 1e-3)}
         out["other_workloads"] = others
         out["planner_steps"] = time_planner_steps(amd, a.config, dev)
+        out["tables_d2h"] = time_d2h(amd, a.config, dev)
     if not a.no_cpu:
         out["cpu_baseline"] = cpu_baseline(a.config)
     else:
