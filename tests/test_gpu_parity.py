@@ -63,6 +63,18 @@ def test_random_shapes(amd, oracle_mod, seed):
     assert_tables_equal(oracle_mod, batch, amd.solve(batch), nthreads=4)
 
 
+@pytest.mark.parametrize("L,M,B,seed,size_hi", [
+    (6, 70000, 2, 31, 9000),      # rows much wider than any tile of m
+    (20, 20000, 1, 32, 1500),
+    (40, 36000, 3, 33, 1200),     # large enough for the two-stream schedule, odd batch split
+    (10, 100, 700, 34, 9),        # more chains than threads of any block
+])
+def test_wide_rows_and_many_chains(amd, oracle_mod, L, M, B, seed, size_hi):
+    batch = random_chain_batch(L, M, B, seed, size_hi=size_hi, time_hi=5000, overheads=True, own_wdelta=True)
+    print(f"case {batch.name}", flush=True)
+    assert_tables_equal(oracle_mod, batch, amd.solve(batch), nthreads=8)
+
+
 def test_everything_infeasible(amd, oracle_mod):
     batch = random_chain_batch(12, 3, 2, 21, size_hi=9)
     batch.wa += 5
