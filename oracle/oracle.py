@@ -269,6 +269,22 @@ def discretize(sizes_bytes, budget_bytes, M):
     return out
 
 
+def budget_sweep(base_budget, alpha_num, alpha_den, count):
+    """Memory budgets of the planner's loop (Section "Integrate Two Solvers"): the budgets
+    (1 + alpha)^n, n = 0..count-1, scaled by a base budget, with alpha = alpha_num / alpha_den:
+    budget_n = floor(base * (1 + alpha)^n), exact (Python integers)."""
+    base, num, den = int(base_budget), int(alpha_num), int(alpha_den)
+    if base <= 0 or num < 0 or den <= 0 or count < 1:
+        raise ValueError("bad sweep")
+    return [base * (den + num) ** n // den ** n for n in range(count)]
+
+
+def discretize_sweep(sizes_bytes, base_budget, alpha_num, alpha_den, count, M):
+    """One profile cut into slots under every budget of the sweep: row n is discretize() of the
+    profile under budget_n."""
+    return [discretize(sizes_bytes, b, M) for b in budget_sweep(base_budget, alpha_num, alpha_den, count)]
+
+
 # Node flags of the linearisation input (one byte per node).
 PLACEHOLDER, COMMON_SEED, NON_DIFF, IN_PLACE, COMM = 1, 2, 4, 8, 16
 

@@ -62,3 +62,31 @@ def test_select_plan_cases(oracle_mod):
     budgets[b] = need - 1
     b3, v3 = oracle_mod.select_plan(tables, L, budgets)
     assert b3 != b and v3 == min(r for k, r in enumerate(roots) if k != b)
+
+
+def test_budget_sweep_closed_forms_and_bracket(oracle_mod):
+    from fractions import Fraction
+    assert oracle_mod.budget_sweep(1000, 0, 1, 5) == [1000] * 5                       # alpha = 0
+    assert oracle_mod.budget_sweep(3, 1, 1, 6) == [3, 6, 12, 24, 48, 96]              # alpha = 1 doubles
+    assert oracle_mod.budget_sweep(1000, 1, 10, 4) == [1000, 1100, 1210, 1331]        # 1.1^n, exact
+    assert oracle_mod.budget_sweep(7, 1, 2, 4) == [7, 10, 15, 23]                     # 7 * 1.5^n = 7, 10.5, 15.75, 23.625
+    for base, num, den in ((80 * 2**30, 1, 10), (12345678901, 3, 20), (1, 1, 8), (999, 7, 100)):
+        got = oracle_mod.budget_sweep(base, num, den, 10)
+        for n, b in enumerate(got):
+            exact = base * (1 + Fraction(num, den)) ** n
+            assert b <= exact < b + 1
+        assert got == sorted(got) and got[0] == base
+    for bad in ((0, 1, 10, 3), (5, -1, 10, 3), (5, 1, 0, 3), (5, 1, 10, 0)):
+        with pytest.raises(ValueError):
+            oracle_mod.budget_sweep(*bad)
+
+
+def test_discretize_sweep_rows_are_single_discretisations(oracle_mod):
+    sizes = [0, 1, 999, 1000, 1001, 123456]
+    rows = oracle_mod.discretize_sweep(sizes, 1000, 1, 10, 4, 100)
+    assert rows[0] == [0, 1, 100, 100, 101, 12346]          # budget 1000: ceil(v / 10)
+    assert rows[1] == [0, 1, 91, 91, 91, 11224]             # budget 1100: ceil(v * 100 / 1100)
+    for row, budget in zip(rows, (1000, 1100, 1210, 1331)):
+        assert row == oracle_mod.discretize(sizes, budget, 100)
+    # a larger budget never needs more slots
+    assert all(a >= b for r0, r1 in zip(rows, rows[1:]) for a, b in zip(r0, r1))
