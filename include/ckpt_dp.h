@@ -194,6 +194,32 @@ int ckpt_discretize(const int64_t* bytes_wa, const int64_t* bytes_wabar, const i
                     int M, int B, void* stream, const ckpt_chains_t* out);
 
 /*
+ * Memory budgets of the planner's loop (Section "Integrate Two Solvers": budgets (1+alpha)^n
+ * for n = 0..9), scaled by a base budget, with alpha = alpha_num / alpha_den:
+ *     budgets[n] = floor(base_budget * (1 + alpha)^n),  n = 0..count-1,  exact.
+ * Host function, host output.  Returns CKPT_OK; CKPT_E_ARG (base_budget <= 0, alpha_num < 0,
+ * alpha_den <= 0, count < 1, NULL); CKPT_E_LIMIT (count > CKPT_MAX_SWEEP, a budget above
+ * 2^63 - 1, or base * (den + num)^n resp. den^n beyond 128 bits).
+ */
+#define CKPT_MAX_SWEEP 16
+int ckpt_budget_sweep(int64_t base_budget, int alpha_num, int alpha_den, int count, int64_t* budgets);
+
+/*
+ * ckpt_discretize of ONE profile under every budget of ckpt_budget_sweep: chain n of the
+ * output holds the profile's sizes in slots of budgets[n] / M bytes, so that the `count`
+ * chains can go to ckpt_solve_batched as one batch.
+ *   bytes_*      DEVICE int64 arrays of one chain ([L+1] resp. [L]); optional ones may be NULL
+ *   budgets_out  DEVICE int64 [count] or NULL: the budgets used
+ *   out          host struct of DEVICE int32 output pointers shaped for B = count chains
+ * Preconditions and limits as for ckpt_discretize and ckpt_budget_sweep.
+ * Returns CKPT_OK, CKPT_E_ARG, CKPT_E_LIMIT or CKPT_E_HIP.
+ */
+int ckpt_discretize_sweep(const int64_t* bytes_wa, const int64_t* bytes_wabar, const int64_t* bytes_wdelta,
+                          const int64_t* bytes_of, const int64_t* bytes_ob, int64_t base_budget, int alpha_num,
+                          int alpha_den, int count, int L, int M, void* stream, int64_t* budgets_out,
+                          const ckpt_chains_t* out);
+
+/*
  * ckpt_schedule for every chain at once, on the device: chain b is walked from cell
  * (1, L, min(m_budget[b], M)).
  *   arg        DEVICE arg table; wa, wabar DEVICE arrays of ckpt_chains_t shape

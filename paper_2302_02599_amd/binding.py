@@ -69,6 +69,11 @@ def load_library():
     lib.ckpt_select_plan.argtypes = [vp, i, i, i, vp, vp, vp]
     lib.ckpt_discretize.restype = i
     lib.ckpt_discretize.argtypes = [vp, vp, vp, vp, vp, vp, i, i, i, vp, ctypes.POINTER(_Chains)]
+    lib.ckpt_budget_sweep.restype = i
+    lib.ckpt_budget_sweep.argtypes = [ctypes.c_int64, i, i, i, vp]
+    lib.ckpt_discretize_sweep.restype = i
+    lib.ckpt_discretize_sweep.argtypes = [vp, vp, vp, vp, vp, ctypes.c_int64, i, i, i, i, i, vp, vp,
+                                          ctypes.POINTER(_Chains)]
     lib.ckpt_schedule_batched.restype = i
     lib.ckpt_schedule_batched.argtypes = [vp, vp, vp, i, i, i, vp, vp, vp, i, vp, vp]
     lib.ckpt_schedule_workspace_bytes.restype, lib.ckpt_schedule_workspace_bytes.argtypes = sz, [i, i]
@@ -227,6 +232,34 @@ def ckpt_discretize(bytes_wa, bytes_wabar, budget_bytes, L, M, B, wa, wabar, *, 
                                         ctypes.byref(outs))
     if rc != 0:
         raise CkptError(rc, "ckpt_discretize")
+
+
+def ckpt_budget_sweep(base_budget: int, alpha_num: int, alpha_den: int, count: int) -> list:
+    """Host: budgets floor(base * (1 + alpha_num/alpha_den)^n), n = 0..count-1."""
+    out = np.zeros(max(count, 1), np.int64)
+    rc = load_library().ckpt_budget_sweep(base_budget, alpha_num, alpha_den, count, out.ctypes.data)
+    if rc != 0:
+        raise CkptError(rc, "ckpt_budget_sweep")
+    return out[:count].tolist()
+
+
+def ckpt_discretize_sweep(bytes_wa, bytes_wabar, base_budget, alpha_num, alpha_den, count, L, M, wa, wabar, *,
+                          bytes_wdelta=None, bytes_of=None, bytes_ob=None, wdelta=None, of=None, ob=None,
+                          budgets_out=None, stream=None) -> None:
+    """One profile (int64 byte sizes of one chain) -> int32 slot sizes of `count` chains, chain n under
+    the n-th budget of the sweep."""
+    import torch
+    i64, i32 = torch.int64, torch.int32
+    B = max(count, 0)
+    outs = _Chains(None, None, _dev(wa, "wa", i32, B * (L + 1)), _dev(wabar, "wabar", i32, B * L),
+                   _dev(wdelta, "wdelta", i32, B * (L + 1)), _dev(of, "of", i32, B * L), _dev(ob, "ob", i32, B * L))
+    rc = load_library().ckpt_discretize_sweep(
+        _dev(bytes_wa, "bytes_wa", i64, L + 1), _dev(bytes_wabar, "bytes_wabar", i64, L),
+        _dev(bytes_wdelta, "bytes_wdelta", i64, L + 1), _dev(bytes_of, "bytes_of", i64, L),
+        _dev(bytes_ob, "bytes_ob", i64, L), base_budget, alpha_num, alpha_den, count, L, M, _stream(stream),
+        _dev(budgets_out, "budgets_out", i64, B), ctypes.byref(outs))
+    if rc != 0:
+        raise CkptError(rc, "ckpt_discretize_sweep")
 
 
 def ckpt_schedule_workspace_bytes(L: int, B: int) -> int:

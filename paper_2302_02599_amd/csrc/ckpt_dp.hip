@@ -594,16 +594,36 @@ __global__ void __launch_bounds__(256) select_kernel(const int32_t* __restrict__
     }
 }
 
-// slots = min(2^31 - 1, ceil(bytes * M / budget)); one thread per element, one chain per blockIdx.y.
+// slots = min(2^31 - 1, ceil(bytes * M / budget))
+__device__ inline int32_t slots_of(long long bytes, unsigned long long budget, int M) {
+    const unsigned long long v = static_cast<unsigned long long>(bytes) * uint32_t(M);
+    const unsigned long long q = budget ? v / budget + (v % budget != 0) : 0x7fffffffull;
+    return int32_t(min(q, 0x7fffffffull));
+}
+
+// One thread per element, one chain per blockIdx.y.
 __global__ void __launch_bounds__(256) discretize_kernel(const long long* __restrict__ in, int32_t* __restrict__ out,
                                                           const long long* __restrict__ budget, int per_chain, int M) {
     const int b = blockIdx.y;
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= per_chain) return;
-    const unsigned long long bud = static_cast<unsigned long long>(budget[b]);
-    const unsigned long long v = static_cast<unsigned long long>(in[size_t(b) * per_chain + k]) * uint32_t(M);
-    const unsigned long long q = bud ? v / bud + (v % bud != 0) : 0x7fffffffull;
-    out[size_t(b) * per_chain + k] = int32_t(min(q, 0x7fffffffull));
+    out[size_t(b) * per_chain + k] =
+        slots_of(in[size_t(b) * per_chain + k], static_cast<unsigned long long>(budget[b]), M);
+}
+
+// The same for one profile under every budget of a sweep: chain blockIdx.y uses budget[blockIdx.y].
+struct SweepBudgets { long long v[CKPT_MAX_SWEEP]; };
+__global__ void __launch_bounds__(256) discretize_sweep_kernel(const long long* __restrict__ in,
+                                                                int32_t* __restrict__ out, SweepBudgets budget,
+                                                                int per_chain, int M) {
+    const int b = blockIdx.y;
+    const int k = blockIdx.x * blockDim.x + threadIdx.x;
+    if (k >= per_chain) return;
+    out[size_t(b) * per_chain + k] = slots_of(in[k], static_cast<unsigned long long>(budget.v[b]), M);
+}
+
+__global__ void __launch_bounds__(64) store_budgets_kernel(SweepBudgets budget, int count, long long* __restrict__ out) {
+    if (int(threadIdx.x) < count) out[threadIdx.x] = budget.v[threadIdx.x];
 }
 
 // One thread per chain walks its recorded candidates with an explicit stack.  Pending work
@@ -981,6 +1001,55 @@ int ckpt_discretize(const int64_t* bytes_wa, const int64_t* bytes_wabar, const i
         hipLaunchKernelGGL(discretize_kernel, dim3((j.n + 255) / 256, B), dim3(256), 0, st,
                            reinterpret_cast<const long long*>(j.in), const_cast<int32_t*>(j.out),
                            reinterpret_cast<const long long*>(budget_bytes), j.n, M);
+        if (!hip_ok(hipGetLastError())) return CKPT_E_HIP;
+    }
+    return CKPT_OK;
+}
+
+int ckpt_budget_sweep(int64_t base_budget, int alpha_num, int alpha_den, int count, int64_t* budgets) {
+    if (base_budget <= 0 || alpha_num < 0 || alpha_den <= 0 || count < 1 || !budgets) return CKPT_E_ARG;
+    if (count > CKPT_MAX_SWEEP) return CKPT_E_LIMIT;
+    // budget_n = floor(base * (den + num)^n / den^n), kept exact in 128 bits
+    const unsigned __int128 limit = ~static_cast<unsigned __int128>(0);
+    const unsigned __int128 grow = static_cast<unsigned __int128>(alpha_num) + static_cast<unsigned>(alpha_den);
+    unsigned __int128 top = static_cast<unsigned __int128>(base_budget), bottom = 1;
+    for (int n = 0; n < count; ++n) {
+        const unsigned __int128 b = top / bottom;
+        if (b > static_cast<unsigned __int128>(INT64_MAX)) return CKPT_E_LIMIT;
+        budgets[n] = static_cast<int64_t>(b);
+        if (n + 1 == count) break;
+        if (top > limit / grow || bottom > limit / static_cast<unsigned>(alpha_den)) return CKPT_E_LIMIT;
+        top *= grow;
+        bottom *= static_cast<unsigned>(alpha_den);
+    }
+    return CKPT_OK;
+}
+
+int ckpt_discretize_sweep(const int64_t* bytes_wa, const int64_t* bytes_wabar, const int64_t* bytes_wdelta,
+                          const int64_t* bytes_of, const int64_t* bytes_ob, int64_t base_budget, int alpha_num,
+                          int alpha_den, int count, int L, int M, void* stream, int64_t* budgets_out,
+                          const ckpt_chains_t* out) {
+    if (!bytes_wa || !bytes_wabar || !out || !out->wa || !out->wabar) return CKPT_E_ARG;
+    if ((bytes_wdelta && !out->wdelta) || (bytes_of && !out->of) || (bytes_ob && !out->ob)) return CKPT_E_ARG;
+    SweepBudgets budget{};
+    static_assert(sizeof(long long) == sizeof(int64_t), "budget words");
+    if (int rc = ckpt_budget_sweep(base_budget, alpha_num, alpha_den, count, reinterpret_cast<int64_t*>(budget.v)))
+        return rc;
+    if (int rc = check_dims(L, M, count)) return rc;
+    if (M > (1 << 20)) return CKPT_E_LIMIT;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    struct Job { const int64_t* in; const int32_t* out; int n; };
+    const Job jobs[5] = {{bytes_wa, out->wa, L + 1}, {bytes_wabar, out->wabar, L}, {bytes_wdelta, out->wdelta, L + 1},
+                         {bytes_of, out->of, L}, {bytes_ob, out->ob, L}};
+    for (const Job& j : jobs) {
+        if (!j.in) continue;
+        hipLaunchKernelGGL(discretize_sweep_kernel, dim3((j.n + 255) / 256, count), dim3(256), 0, st,
+                           reinterpret_cast<const long long*>(j.in), const_cast<int32_t*>(j.out), budget, j.n, M);
+        if (!hip_ok(hipGetLastError())) return CKPT_E_HIP;
+    }
+    if (budgets_out) {
+        hipLaunchKernelGGL(store_budgets_kernel, dim3(1), dim3(64), 0, st, budget, count,
+                           reinterpret_cast<long long*>(budgets_out));
         if (!hip_ok(hipGetLastError())) return CKPT_E_HIP;
     }
     return CKPT_OK;

@@ -153,3 +153,38 @@ def test_planner_steps_reject_bad_arguments_before_touching_the_gpu(amd):
     assert g(256, 256, 256, 4, 8, 1, 256, None, 256, 10, 256, 264) == -1                # misaligned workspace
     assert g(256, 256, 256, 4, 8, 1, 256, None, 256, -1, 256, 256) == -1
     assert amd.ckpt_schedule_workspace_bytes(8, 3) == 3 * 18 * 16 and amd.ckpt_schedule_workspace_bytes(0, 3) == 0
+    h = lib.ckpt_simulate_batched
+    chains = _Chains(256, 256, 256, 256, None, None, None)
+    assert h(ctypes.byref(chains), 4, 1, None, 10, 256, None, 256, 256, 256) == -1              # no list
+    assert h(ctypes.byref(chains), 0, 1, 256, 10, 256, None, 256, 256, 256) == -1
+    assert h(ctypes.byref(chains), 255, 1, 256, 10, 256, None, 256, 256, 256) == -2
+    w = lib.ckpt_discretize_sweep
+    assert w(256, 256, None, None, None, 1000, 1, 10, 4, 4, 8, None, None, None) == -1           # no outputs
+    assert w(256, 256, None, None, None, 0, 1, 10, 4, 4, 8, None, None, ctypes.byref(outs)) == -1
+    assert w(256, 256, None, None, None, 1000, 1, 10, 17, 4, 8, None, None, ctypes.byref(outs)) == -2
+
+
+def test_budget_sweep_on_the_host(amd, oracle_mod):
+    """Host arithmetic of the sweep against the oracle's exact integers."""
+    rng = np.random.default_rng(12)
+    cases = [(1000, 1, 10, 10), (80 << 30, 1, 10, 10), (1, 0, 1, 16), (3, 1, 1, 16), (7, 1, 2, 4),
+             ((1 << 62) - 5, 0, 7, 3), (12345678901, 3, 20, 10)]
+    for _ in range(200):
+        cases.append((int(rng.integers(1, 1 << 45)), int(rng.integers(0, 60)), int(rng.integers(1, 101)),
+                      int(rng.integers(1, 11))))
+    lib = amd.load_library()
+    out = np.zeros(32, np.int64)
+    fits = 0
+    for base, num, den, count in cases:
+        want = oracle_mod.budget_sweep(base, num, den, count)
+        if want[-1] < 1 << 63:
+            assert amd.ckpt_budget_sweep(base, num, den, count) == want, (base, num, den, count)
+            fits += 1
+        else:   # a budget that does not fit 64 bits is refused, not wrapped
+            assert lib.ckpt_budget_sweep(base, num, den, count, out.ctypes.data) == -2, (base, num, den, count)
+    assert fits > 100
+    for args, want in (((0, 1, 10, 3), -1), ((5, -1, 10, 3), -1), ((5, 1, 0, 3), -1), ((5, 1, 10, 0), -1),
+                       ((5, 1, 10, 17), -2), ((1 << 62, 1, 1, 3), -2), ((1 << 40, 1 << 30, 1, 16), -2),
+                       ((1 << 40, 0, 1 << 30, 16), -2)):
+        assert lib.ckpt_budget_sweep(*args, out.ctypes.data) == want, args
+    assert lib.ckpt_budget_sweep(5, 1, 10, 3, None) == -1

@@ -263,3 +263,56 @@ def test_simulate_batched_edited_lists(amd, oracle_mod):
         assert (time[b], peak[b], status[b]) == want, (b, lists[b])
         kinds.add(status[b])
     assert kinds == {0, -1, -3, -7}
+
+
+@pytest.mark.parametrize("L,M,count,base,num,den,seed", [
+    (1, 1, 1, 5, 0, 1, 0), (7, 64, 10, 1000, 1, 10, 1), (48, 1024, 10, 80 << 30, 1, 10, 2),
+    (192, 4096, 16, 1 << 33, 1, 8, 3), (33, 1 << 20, 5, 12345678901, 3, 20, 4),
+])
+def test_discretize_sweep(amd, oracle_mod, L, M, count, base, num, den, seed):
+    """One profile under every budget of the sweep: each output chain equals the oracle's
+    discretisation of the profile under that budget, and the budgets equal the oracle's."""
+    import torch
+    rng = np.random.default_rng(seed)
+    big = min(1 << 41, 4 * base)
+    profile = {"wa": rng.integers(0, big, L + 1), "wabar": rng.integers(0, big, L),
+               "wdelta": rng.integers(0, 1 << 20, L + 1), "of": rng.integers(0, 3, L), "ob": rng.integers(0, big, L)}
+    profile["wabar"][0] = base                       # exactly the first budget -> M slots in chain 0
+    dev = {k: torch.from_numpy(v.astype(np.int64)).cuda() for k, v in profile.items()}
+    outs = {k: torch.full((count,) + v.shape, -1, dtype=torch.int32, device="cuda") for k, v in profile.items()}
+    budgets = torch.full((count,), -1, dtype=torch.int64, device="cuda")
+    amd.ckpt_discretize_sweep(dev["wa"], dev["wabar"], base, num, den, count, L, M, outs["wa"], outs["wabar"],
+                              bytes_wdelta=dev["wdelta"], bytes_of=dev["of"], bytes_ob=dev["ob"],
+                              wdelta=outs["wdelta"], of=outs["of"], ob=outs["ob"], budgets_out=budgets)
+    assert budgets.cpu().tolist() == oracle_mod.budget_sweep(base, num, den, count)
+    for k, v in profile.items():
+        assert outs[k].cpu().numpy().tolist() == oracle_mod.discretize_sweep(v.tolist(), base, num, den, count, M), k
+    assert outs["wabar"][0, 0].item() == M
+
+
+def test_discretize_sweep_feeds_the_solver(amd, oracle_mod):
+    """The sweep's output is a batch as ckpt_solve_batched takes it: tables equal the oracle's on
+    the oracle's own discretisation of the same profile."""
+    import torch
+    L, M, count = 12, 200, 6
+    rng = np.random.default_rng(9)
+    by_wa, by_wabar = rng.integers(1 << 20, 1 << 24, L + 1), rng.integers(1 << 24, 1 << 26, L)
+    base = 300 << 20
+    wa = torch.empty((count, L + 1), dtype=torch.int32, device="cuda")
+    wabar = torch.empty((count, L), dtype=torch.int32, device="cuda")
+    amd.ckpt_discretize_sweep(torch.from_numpy(by_wa).cuda(), torch.from_numpy(by_wabar).cuda(), base, 1, 4, count,
+                              L, M, wa, wabar)
+    uf = rng.integers(1, 1000, (count, L)).astype(np.int32)
+    ub = (2 * uf + rng.integers(0, 100, (count, L))).astype(np.int32)
+    batch = ChainBatch("sweep", L, M, count, uf, ub, wa.cpu().numpy(), wabar.cpu().numpy())
+    sol = amd.solve(batch)
+    want_wa = oracle_mod.discretize_sweep(by_wa.tolist(), base, 1, 4, count, M)
+    want_wabar = oracle_mod.discretize_sweep(by_wabar.tolist(), base, 1, 4, count, M)
+    iu = np.triu_indices(L)
+    feasible = 0
+    for b in range(count):
+        cost, choice = oracle_mod.solve_chain(L, M, uf[b], ub[b], want_wa[b], want_wabar[b])
+        assert (sol.cost[b, :, :M + 1].cpu().numpy() == cost[iu]).all()
+        assert (sol.arg[b, :, :M + 1].cpu().numpy() == choice[iu]).all()
+        feasible += int(cost[0, L - 1, M] < oracle_mod.INF)
+    assert 0 < feasible  # the larger budgets of the sweep make the whole chain fit
