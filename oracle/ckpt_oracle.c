@@ -11,7 +11,7 @@
  * that back-propagates through stages s..t with m memory slots, for every
  * 1 <= s <= t <= L and every m in 0..M, plus the candidate that attains it.
  *
- * Readings taken where the paper leaves a choice (all listed in the design doc):
+ * Readings taken where the paper leaves a choice:
  *   - u_f and u_b arrive with the communication times of Table 2 already added,
  *     o_f and o_b with the communication overheads already added.
  *   - "infinity" is the sentinel 2^30; a value is min(2^30, exact sum), so any
