@@ -29,6 +29,13 @@
  * over every persistent schedule for L <= 6 through an independent operation
  * simulator, the unlimited-memory closed form, monotonicity in m, the
  * infeasibility bound, an independent scalar minimum-memory recursion.
+ *
+ * Parity unpinned: (i) the m_null gate of the checkpoint branch -- when every
+ * omega_abar is at least its omega_a the gate is implied by the feasibility of
+ * the operands, so no schedule-level check can see it; it is only compared with
+ * the peak of the simulated forward sweep.  (ii) Inputs with an omega_abar
+ * below its omega_a: the table follows the printed formulas and is compared
+ * only with a second, separately written evaluation of those formulas.
  */
 #include <stdint.h>
 #include <stdlib.h>
