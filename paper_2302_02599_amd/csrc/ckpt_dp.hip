@@ -622,7 +622,8 @@ __global__ void __launch_bounds__(256) discretize_sweep_kernel(const long long* 
     out[size_t(b) * per_chain + k] = slots_of(in[k], static_cast<unsigned long long>(budget.v[b]), M);
 }
 
-__global__ void __launch_bounds__(64) store_budgets_kernel(SweepBudgets budget, int count, long long* __restrict__ out) {
+__global__ void __launch_bounds__(64) store_budgets_kernel(SweepBudgets budget, int count,
+                                                            long long* __restrict__ out) {
     if (int(threadIdx.x) < count) out[threadIdx.x] = budget.v[threadIdx.x];
 }
 
@@ -631,7 +632,8 @@ __global__ void __launch_bounds__(64) store_budgets_kernel(SweepBudgets budget, 
 __global__ void __launch_bounds__(64) schedule_kernel(const uint8_t* __restrict__ arg, const int32_t* __restrict__ wa,
                                                        const int32_t* __restrict__ wabar, int L, int M, int pitch,
                                                        int rows, int B, const int32_t* __restrict__ m_budget,
-                                                       ckpt_op_t* __restrict__ ops, int cap, int32_t* __restrict__ n_ops,
+                                                       ckpt_op_t* __restrict__ ops, int cap,
+                                                       int32_t* __restrict__ n_ops,
                                                        int4* __restrict__ stack_mem) {
     const int b = blockIdx.x * blockDim.x + threadIdx.x;
     if (b >= B) return;
@@ -852,56 +854,64 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     if (side) lock = std::unique_lock<std::mutex>(side->busy);  // one fork/join at a time per device
     hipStream_t s2 = side ? side->stream : st;
 
-    hipLaunchKernelGGL(precompute_kernel, dim3(B), dim3(256), 0, st, *chains, L, pitch, ws);
-    CKPT_AFTER_LAUNCH(CKPT_K_PRECOMPUTE);
-    if (side && (!hip_ok(hipEventRecord(side->fork, st)) || !hip_ok(hipStreamWaitEvent(s2, side->fork, 0))))
-        return CKPT_E_HIP;
-    hipLaunchKernelGGL(frontier_kernel, dim3(B), dim3(1024), frontier_lds, s2, *chains, L, ws);
-    CKPT_AFTER_LAUNCH(CKPT_K_FRONTIER);
+    bool forked = false;
+    auto enqueue = [&]() -> int {
+        hipLaunchKernelGGL(precompute_kernel, dim3(B), dim3(256), 0, st, *chains, L, pitch, ws);
+        CKPT_AFTER_LAUNCH(CKPT_K_PRECOMPUTE);
+        if (side) {
+            if (!hip_ok(hipEventRecord(side->fork, st)) || !hip_ok(hipStreamWaitEvent(s2, side->fork, 0)))
+                return CKPT_E_HIP;
+            forked = true;
+        }
+        hipLaunchKernelGGL(frontier_kernel, dim3(B), dim3(1024), frontier_lds, s2, *chains, L, ws);
+        CKPT_AFTER_LAUNCH(CKPT_K_FRONTIER);
 
-    auto launch_rows = [&](int D, int b0, int nb, hipStream_t s) -> int {
-        const Ctx ctx{L, M, pitch, rows, b0, ws, cost, arg};
-        const auto& rowfn = D == 0 ? kRow0 : (D == 1 ? kRow1 : kRow2);
-        for (int r = T - 1; r >= 0; --r) {
-            hipLaunchKernelGGL(rowfn[r], dim3(gx_row, nblk - D, nb), dim3(kRowWG), 0, s, ctx, D);
-            CKPT_AFTER_LAUNCH(CKPT_K_ROW);
+        auto launch_rows = [&](int D, int b0, int nb, hipStream_t s) -> int {
+            const Ctx ctx{L, M, pitch, rows, b0, ws, cost, arg};
+            const auto& rowfn = D == 0 ? kRow0 : (D == 1 ? kRow1 : kRow2);
+            for (int r = T - 1; r >= 0; --r) {
+                hipLaunchKernelGGL(rowfn[r], dim3(gx_row, nblk - D, nb), dim3(kRowWG), 0, s, ctx, D);
+                CKPT_AFTER_LAUNCH(CKPT_K_ROW);
+            }
+            return CKPT_OK;
+        };
+        for (int D = 0; D < 2 && D < nblk; ++D)
+            if (int rc = launch_rows(D, 0, B, st)) return rc;
+        if (side) {
+            // both streams wait for each other: the frontier is done, and so are the D < 2 rows
+            if (!hip_ok(hipEventRecord(side->join, s2)) || !hip_ok(hipStreamWaitEvent(st, side->join, 0)) ||
+                !hip_ok(hipEventRecord(side->fork, st)) || !hip_ok(hipStreamWaitEvent(s2, side->fork, 0)))
+                return CKPT_E_HIP;
+        }
+        const int groups = side ? 2 : 1;
+        const int first[3] = {0, side ? B / 2 : B, B};
+        hipStream_t gs[2] = {st, s2};
+        for (int D = 2; D < nblk; ++D) {
+            for (int g = 0; g < groups; ++g) {
+                const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
+                hipLaunchKernelGGL((gemm_kernel<3, 3, kCH>), dim3(gx_gemm, nblk - D, first[g + 1] - first[g]),
+                                   dim3(64 * kCH), 0, gs[g], ctx, D);
+                CKPT_AFTER_LAUNCH(CKPT_K_GEMM);
+            }
+            // rows of the two halves are issued alternately so that both queues stay fed
+            const auto& rowfn = kRow2;
+            for (int r = T - 1; r >= 0; --r) {
+                for (int g = 0; g < groups; ++g) {
+                    const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
+                    hipLaunchKernelGGL(rowfn[r], dim3(gx_row, nblk - D, first[g + 1] - first[g]), dim3(kRowWG), 0,
+                                       gs[g], ctx, D);
+                    CKPT_AFTER_LAUNCH(CKPT_K_ROW);
+                }
+            }
         }
         return CKPT_OK;
     };
-    for (int D = 0; D < 2 && D < nblk; ++D)
-        if (int rc = launch_rows(D, 0, B, st)) return rc;
-    if (side) {
-        // both streams wait for each other: the frontier is done, and so are the D < 2 rows
-        if (!hip_ok(hipEventRecord(side->join, s2)) || !hip_ok(hipStreamWaitEvent(st, side->join, 0)) ||
-            !hip_ok(hipEventRecord(side->fork, st)) || !hip_ok(hipStreamWaitEvent(s2, side->fork, 0)))
-            return CKPT_E_HIP;
-    }
-    const int groups = side ? 2 : 1;
-    const int first[3] = {0, side ? B / 2 : B, B};
-    hipStream_t gs[2] = {st, s2};
-    for (int D = 2; D < nblk; ++D) {
-        for (int g = 0; g < groups; ++g) {
-            const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
-            hipLaunchKernelGGL((gemm_kernel<3, 3, kCH>), dim3(gx_gemm, nblk - D, first[g + 1] - first[g]),
-                               dim3(64 * kCH), 0, gs[g], ctx, D);
-            CKPT_AFTER_LAUNCH(CKPT_K_GEMM);
-        }
-        // rows of the two halves are issued alternately so that both queues stay fed
-        const auto& rowfn = kRow2;
-        for (int r = T - 1; r >= 0; --r) {
-            for (int g = 0; g < groups; ++g) {
-                const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
-                hipLaunchKernelGGL(rowfn[r], dim3(gx_row, nblk - D, first[g + 1] - first[g]), dim3(kRowWG), 0, gs[g],
-                                   ctx, D);
-                CKPT_AFTER_LAUNCH(CKPT_K_ROW);
-            }
-        }
-    }
-    if (side) {
-        if (!hip_ok(hipEventRecord(side->join, s2)) || !hip_ok(hipStreamWaitEvent(st, side->join, 0)))
-            return CKPT_E_HIP;
-    }
-    return CKPT_OK;
+    const int rc = enqueue();
+    // The second stream always rejoins the caller's stream, also after a failed launch, so that
+    // the caller's stream (or a capture in progress) is never left with an open fork.
+    if (forked && (!hip_ok(hipEventRecord(side->join, s2)) || !hip_ok(hipStreamWaitEvent(st, side->join, 0))))
+        return rc ? rc : CKPT_E_HIP;
+    return rc;
 }
 
 }  // namespace
