@@ -264,6 +264,17 @@ __device__ __forceinline__ uint32_t ld32(rsrc_t tab, uint32_t elem, uint32_t off
     return uint32_t(__builtin_amdgcn_raw_buffer_load_b32(tab, int(off), int(elem << 2), 0));
 }
 
+// Work-groups go to the 8 XCDs round-robin by linear index x + gx * t (t = tile and chain), and
+// the cost of a chunk of m grows with m (low budgets are infeasible and skipped).  If chunk = x,
+// the chunks that XCD k gets satisfy chunk = k - gx * t (mod 8): with an even gx they miss
+// residues, e.g. for gx = 16 the last XCD gets chunks 7 and 15 of every tile, the expensive
+// ones.  Rotating the chunk by t turns this into chunk = k + (1 - gx) * t (mod 8): for an even
+// gx every XCD then meets every residue; an odd gx has that property without rotation.
+__device__ __forceinline__ uint32_t rotated_block_x() {
+    if (gridDim.x & 1u) return blockIdx.x;
+    return (blockIdx.x + blockIdx.y + gridDim.y * blockIdx.z) % gridDim.x;
+}
+
 // Middle splits of every tile of block diagonal D >= 2.
 // One wave owns the 8x8 tile of cells for 64 consecutive m; lane = m.  Each loaded operand
 // row is used by 8 cells (1 byte of table traffic per candidate instead of 8).  The CH waves of
@@ -285,9 +296,10 @@ __global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
     const int j0 = J * T, i0 = I * T;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
-    const int chunk = blockIdx.x * CH + wave;  // this wave's 64 columns of m
+    const int bx = int(rotated_block_x());
+    const int chunk = bx * CH + wave;  // this wave's 64 columns of m
     const uint32_t m = chunk * 64 + lane;
-    const int m_hi = min(int(blockIdx.x * CH + CH) * 64, pitch) - 1;  // largest m of the work-group
+    const int m_hi = min((bx * CH + CH) * 64, pitch) - 1;  // largest m of the work-group
     const uint32_t moff = m * 4;
     const size_t chain = size_t(b) * c.rows * pitch;
     const rsrc_t tab = table_rsrc(c.cost + chain, uint32_t(c.rows) * uint32_t(pitch) * 4u);
@@ -430,7 +442,7 @@ __global__ void __launch_bounds__(kRowWG) row_kernel(Ctx c, int D) {
     const int L = c.L, pitch = c.pitch;
     const int i = I * T + R;
     if (i >= L) return;
-    const uint32_t m = blockIdx.x * kRowWG + threadIdx.x;
+    const uint32_t m = rotated_block_x() * kRowWG + threadIdx.x;
     if (m >= uint32_t(pitch)) return;
     const uint32_t moff = m * 4;
     const size_t chain = size_t(b) * c.rows * pitch;
