@@ -264,15 +264,18 @@ __device__ __forceinline__ uint32_t ld32(rsrc_t tab, uint32_t elem, uint32_t off
     return uint32_t(__builtin_amdgcn_raw_buffer_load_b32(tab, int(off), int(elem << 2), 0));
 }
 
-// Work-groups go to the 8 XCDs round-robin by linear index x + gx * t (t = tile and chain), and
-// the cost of a chunk of m grows with m (low budgets are infeasible and skipped).  If chunk = x,
-// the chunks that XCD k gets satisfy chunk = k - gx * t (mod 8): with an even gx they miss
-// residues, e.g. for gx = 16 the last XCD gets chunks 7 and 15 of every tile, the expensive
-// ones.  Rotating the chunk by t turns this into chunk = k + (1 - gx) * t (mod 8): for an even
-// gx every XCD then meets every residue; an odd gx has that property without rotation.
-__device__ __forceinline__ uint32_t rotated_block_x() {
-    if (gridDim.x & 1u) return blockIdx.x;
-    return (blockIdx.x + blockIdx.y + gridDim.y * blockIdx.z) % gridDim.x;
+// Which (chunk of m, tile, chain) a work-group takes.  The hardware hands work-groups out in
+// linear order and to the 8 XCDs round-robin, and the cost of a chunk grows with m (low budgets
+// are infeasible and skipped).  The linear index is therefore re-read as (tile and chain)
+// fastest, chunk slowest and descending: the expensive chunks of all tiles start first and
+// the cheap ones fill the tail of the launch, and at every chunk level the tiles and chains
+// spread evenly over the XCDs.
+struct Work { int chunk, tile, chain; };
+__device__ __forceinline__ Work work_of_block() {
+    const uint32_t nt = gridDim.y * gridDim.z;
+    const uint32_t lin = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const uint32_t level = lin / nt, t = lin - level * nt;
+    return {int(gridDim.x - 1 - level), int(t % gridDim.y), int(t / gridDim.y)};
 }
 
 // Middle splits of every tile of block diagonal D >= 2.
@@ -290,13 +293,14 @@ template <int NB, int UNR, int CH>
 __global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
     constexpr int T = kT;
     static_assert(T == 8, "one wave per 8x8 tile");
-    const int b = c.b0 + blockIdx.z, I = blockIdx.y, J = I + D;
+    const Work w = work_of_block();
+    const int b = c.b0 + w.chain, I = w.tile, J = I + D;
     const int L = c.L, pitch = c.pitch;
     const int qlo = (I + 1) * T, qhi = J * T;
     const int j0 = J * T, i0 = I * T;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
-    const int bx = int(rotated_block_x());
+    const int bx = w.chunk;
     const int chunk = bx * CH + wave;  // this wave's 64 columns of m
     const uint32_t m = chunk * 64 + lane;
     const int m_hi = min((bx * CH + CH) * 64, pitch) - 1;  // largest m of the work-group
@@ -438,11 +442,12 @@ __global__ void __launch_bounds__(kRowWG) row_kernel(Ctx c, int D) {
     constexpr int CF = (DC == 0) ? R : 0;                              // first column with j >= i
     constexpr int NQ = (DC == 0) ? 0 : (DC == 1 ? T - R : T - 1 - R);  // near-i splits (D = 1: and q = jb)
     constexpr int NQA = NQ > 0 ? NQ : 1;
-    const int b = c.b0 + blockIdx.z, I = blockIdx.y, J = I + D;
+    const Work w = work_of_block();
+    const int b = c.b0 + w.chain, I = w.tile, J = I + D;
     const int L = c.L, pitch = c.pitch;
     const int i = I * T + R;
     if (i >= L) return;
-    const uint32_t m = rotated_block_x() * kRowWG + threadIdx.x;
+    const uint32_t m = uint32_t(w.chunk) * kRowWG + threadIdx.x;
     if (m >= uint32_t(pitch)) return;
     const uint32_t moff = m * 4;
     const size_t chain = size_t(b) * c.rows * pitch;
