@@ -24,9 +24,11 @@ sys.path.insert(0, ROOT)
 # vector peak counts an FMA as two), and so do 32-bit integer operations.
 PEAK_HBM = 8.0e12
 PEAK_VALU_OPS = 256 * 64 * 2.4e9
-# Algorithmic work of gemm_kernel per candidate: 16 operand rows of 4 B feed an 8x8 tile of
-# cells, i.e. 1 byte of table reads per candidate, plus 5 bytes (cost + candidate number) of
-# partial result per cell; one float64 add and one float64 min per candidate.
+# Algorithmic work of gemm_kernel per candidate of the middle splits: 16 operand rows of 4 B feed
+# an 8x8 tile of cells, i.e. 1 byte of table reads per candidate; one float64 add and one float64
+# min per candidate.  Every cell of the tile costs 5 bytes stored (cost + candidate number: the
+# partial result for rows 0..6, the finished cell for row 7), and row 7, which the kernel finishes
+# itself, one 4-byte operand load per split in the column block and per C_all.
 GEMM_BYTES_PER_EVAL = 1.0
 GEMM_BYTES_PER_CELL = 5.0
 GEMM_OPS_PER_EVAL = 2
@@ -38,42 +40,54 @@ def counts(L, M, B):
     return cells, evals
 
 
+def row_loads(L, T, D, I, r):
+    """(operand loads, stored cells) of one lane finishing row r of tile (I, I + D): 9 loads per
+    split in the row block (left + 8 right; clamped columns are loaded too), one per split in the
+    column block, one C_all operand per cell with j > i."""
+    J, i = I + D, I * T + r
+    cols = [j for j in range(J * T, min(L, J * T + T)) if j >= i]
+    near_i = 0 if D == 0 else ((T - r) if D == 1 else (T - 1 - r))
+    loads = near_i * (1 + T)
+    loads += sum(1 for j in cols for q in range(max(i + 1, J * T + 1), j + 1))
+    loads += sum(1 for j in cols if j > i)
+    return loads, len(cols)
+
+
 def gemm_work(L, M, B, T=8):
-    """(candidates, cells) handled by gemm_kernel per step: for every tile of block diagonal
-    D >= 2 the splits strictly between its row block and its column block, plus the first
-    stage of the column block.  Nominal counts: candidates that the feasibility test drops
-    still count, as infeasible cells do in the headline metric."""
+    """(middle candidates, cells, row-7 operand loads) of gemm_kernel per step: for every tile of
+    block diagonal D >= 2 the splits strictly between its row block and its column block, plus
+    the first stage of the column block; and the loads with which it finishes row 7.  Nominal
+    counts: candidates that the feasibility test drops still count, as infeasible cells do in
+    the headline metric."""
     nblk = (L + T - 1) // T
-    evals = cells = 0
+    evals = cells = loads7 = 0
     for D in range(2, nblk):
         for I in range(nblk - D):
             cols = min(T, L - (I + D) * T)
             cells += T * cols
             evals += T * cols * ((D - 1) * T + 1)
-    return evals * (M + 1) * B, cells * (M + 1) * B
+            loads7 += row_loads(L, T, D, I, T - 1)[0]
+    return evals * (M + 1) * B, cells * (M + 1) * B, loads7 * (M + 1) * B
+
+
+def gemm_bytes(L, M, B, T=8):
+    evals, cells, loads7 = gemm_work(L, M, B, T)
+    return GEMM_BYTES_PER_EVAL * evals + GEMM_BYTES_PER_CELL * cells + 4 * loads7
 
 
 def row_bytes(L, M, B, T=8):
     """Algorithmic bytes of all row_kernel launches of a step (nominal: waves that the frontier
-    test skips still count).  Per lane and row r of a tile: 9 loads per near-i split (left + 8
-    right), 5 bytes per cell of gemm partial (D >= 2), one load per near-j candidate, one C_all
-    operand per cell with j > i, and 5 bytes stored per cell."""
+    test skips still count): 4 bytes per operand load, 5 bytes per cell of gemm partial (D >= 2)
+    and 5 bytes stored per cell.  Row 7 of the tiles of D >= 2 belongs to gemm_kernel."""
     nblk = (L + T - 1) // T
     total = 0
     for D in range(nblk):
         for I in range(nblk - D):
-            J = I + D
             for r in range(T):
-                i = I * T + r
-                if i >= L:
+                if I * T + r >= L or (D >= 2 and r == T - 1):
                     continue
-                cols = [j for j in range(J * T, min(L, J * T + T)) if j >= i]
-                near_i = 0 if D == 0 else ((T - r) if D == 1 else (T - 1 - r))
-                loads = near_i * (1 + T)                                   # clamped columns are loaded too
-                loads += sum(1 for j in cols for q in range(max(i + 1, J * T + 1), j + 1))   # near-j
-                loads += sum(1 for j in cols if j > i)                     # C_all
-                nbytes = 4 * loads + (5 * T if D >= 2 else 0) + 5 * len(cols)
-                total += nbytes
+                loads, stored = row_loads(L, T, D, I, r)
+                total += 4 * loads + (5 * T if D >= 2 else 0) + 5 * stored
     return total * (M + 1) * B
 
 
@@ -274,17 +288,17 @@ def main():
     evals_per_s = r["evals"] / (r["ms"] * 1e-3)
     kinds = r["kinds"]
     dom = max(("gemm_kernel", "row_kernel"), key=lambda k: kinds[k]["ms_per_step"])
-    gemm_evals, gemm_cells = gemm_work(batch.L, batch.M, batch.B)
+    gemm_evals, _, gemm_loads7 = gemm_work(batch.L, batch.M, batch.B)
     dom_ms = kinds[dom]["ms_per_step"]
     launches = max(1, kinds[dom]["launches_per_step"])
     per_launch_s = dom_ms * 1e-3 / launches
     if dom == "gemm_kernel":
-        alg_bytes = (GEMM_BYTES_PER_EVAL * gemm_evals + GEMM_BYTES_PER_CELL * gemm_cells) / launches
-        dom_evals, ops_per_eval = gemm_evals, GEMM_OPS_PER_EVAL
+        alg_bytes = gemm_bytes(batch.L, batch.M, batch.B) / launches
+        dom_evals, ops_per_eval = gemm_evals, GEMM_OPS_PER_EVAL   # the middle splits; row 7 adds < 1 %
         alu_unit = "Tlane-op/s (float64 add + min per candidate)"
     else:
         alg_bytes = row_bytes(batch.L, batch.M, batch.B) / launches
-        dom_evals, ops_per_eval = r["evals"] - gemm_evals, 4     # add, compare, two selects per candidate
+        dom_evals, ops_per_eval = r["evals"] - gemm_evals - gemm_loads7, 4   # add, compare, two selects each
         alu_unit = "Tlane-op/s (32-bit add, compare, two selects per candidate)"
     alg_ops = ops_per_eval * dom_evals / launches
     roofline = {"bound": "hbm", "kernel": dom, "achieved": alg_bytes / per_launch_s / 1e9, "peak": PEAK_HBM / 1e9,

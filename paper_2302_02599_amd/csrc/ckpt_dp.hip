@@ -278,6 +278,70 @@ __device__ __forceinline__ Work work_of_block() {
     return {int(gridDim.x - 1 - level), int(t % gridDim.y), int(t / gridDim.y)};
 }
 
+// + j = table row of cell (q, j)
+__device__ __forceinline__ int row_base(int L, int q) { return q * L - (q * (q - 1)) / 2 - q; }
+
+// Operands of the part of a row that does not depend on the row block: the splits in the
+// column block (right operand (jb + c2 + 1, j) at its shift, for CF <= c2 < cc) and C_all (right
+// operand (i + 1, j) at m - omega_abar^{i+1}).
+template <int T, int CF>
+__device__ __forceinline__ void load_row_tail(rsrc_t tab, const int32_t* __restrict__ wsh, int L, int pitch, int i,
+                                              int jb, const int (&jc)[T], uint32_t wabi, uint32_t moff,
+                                              uint32_t (&tj)[T][T], uint32_t (&al)[T]) {
+#pragma unroll
+    for (int cc = CF + 1; cc < T; ++cc)
+#pragma unroll
+        for (int c2 = CF; c2 < cc; ++c2) {
+            const int q = min(jb + c2 + 1, L - 1);
+            tj[c2][cc] = ld32(tab, uint32_t(row_base(L, q) + jc[cc]) * uint32_t(pitch) - uint32_t(wsh[q]), moff);
+        }
+#pragma unroll
+    for (int cc = CF; cc < T; ++cc) {
+        const int i1 = min(i + 1, L - 1);
+        al[cc] = ld32(tab, uint32_t(row_base(L, i1) + max(jc[cc], i1)) * uint32_t(pitch) - wabi, moff);
+    }
+}
+
+// Finishes the cells of row i in column block jb from the best candidate so far (splits in the
+// row block, gemm partial): splits in the column block with the left operand (i, q-1) = the
+// cell just finished, then the m_null gate, C_all with the m_all gate (smallest candidate
+// number: wins ties), saturation, store.
+template <int T, int CF, int DC>
+__device__ __forceinline__ void finish_row(const Ctx& c, size_t chain, const int32_t* __restrict__ P,
+                                           const int32_t* __restrict__ mall, const int32_t* __restrict__ mnull,
+                                           int L, int pitch, int i, int jb, int cend, const int (&jc)[T],
+                                           uint32_t fbi, uint32_t m, uint32_t (&best)[T], uint32_t (&pick)[T],
+                                           const uint32_t (&tj)[T][T], const uint32_t (&al)[T]) {
+    const uint32_t Pi = P[i];
+    const int rowi = tri_row(L, i, i) - i;  // + j = row of (i, j)
+    uint32_t val[T];
+#pragma unroll
+    for (int cc = 0; cc < T; ++cc) val[cc] = kInf;
+#pragma unroll
+    for (int cc = CF; cc < T; ++cc) {
+        const int j = jc[cc];
+#pragma unroll
+        for (int c2 = CF; c2 < cc; ++c2) {
+            const int q = min(jb + c2 + 1, L - 1);  // left operand (i, q-1) = val[c2]
+            const uint32_t v = val[c2] + (uint32_t(P[q]) - Pi) + tj[c2][cc];
+            if (v < best[cc]) best[cc] = v, pick[cc] = q + 1;
+        }
+        const uint32_t ck = (m >= uint32_t(mnull[j])) ? min(best[cc], kInf) : kInf;
+        uint32_t all = fbi;
+        if (DC != 0 || cc > CF) all += al[cc];  // j > i
+        all = (m >= uint32_t(mall[j])) ? min(all, kInf) : kInf;
+        const bool take_all = all < kInf && all <= ck;
+        const uint32_t fin = take_all ? all : ck;
+        const uint32_t fpk = take_all ? uint32_t(i + 1) : (ck < kInf ? pick[cc] : 0u);
+        val[cc] = fin;
+        if (cc < cend) {
+            const size_t o = chain + size_t(rowi + j) * pitch + m;
+            c.cost[o] = int32_t(fin);
+            c.arg[o] = uint8_t(fpk);
+        }
+    }
+}
+
 // Middle splits of every tile of block diagonal D >= 2.
 // One wave owns the 8x8 tile of cells for 64 consecutive m; lane = m.  Each loaded operand
 // row is used by 8 cells (1 byte of table traffic per candidate instead of 8).  The CH waves of
@@ -288,7 +352,9 @@ __device__ __forceinline__ Work work_of_block() {
 // (all values are integers below 2^34 scaled by 2^-8, exact in float64).
 // Splits whose operands are infeasible for the whole chunk (frontier test) are dropped
 // from the work list before the pipeline starts.
-// Output: cost[] <- unsaturated partial minimum (0xffffffff if none), arg[] <- its number.
+// Output, rows 0..6 of the tile: cost[] <- unsaturated partial minimum (0xffffffff if none),
+// arg[] <- its number; row_kernel finishes them.  Row 7 has no split in its own row block, so
+// its partial minimum stays in registers and the wave finishes the row itself.
 template <int NB, int UNR, int CH>
 __global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
     constexpr int T = kT;
@@ -413,18 +479,51 @@ __global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
     }
 
     const int32_t* P = c.ws.P + size_t(b) * (L + 1);
+    // Row 7: operands of its column-block splits and of C_all are requested before the other rows
+    // are converted and stored -- unless the whole chunk lies below the frontier of its cells.
+    const int i7 = i0 + 7;
+    const int cend = min(8, L - j0);
+    int need7 = 1 << 30;
 #pragma unroll
-    for (int r = 0; r < 8; ++r) {
+    for (int cc = 0; cc < 8; ++cc) need7 = min(need7, need[i7 * L + jcol[cc]]);
+    const bool live7 = int(m | 63u) >= need7;  // wave-uniform
+    uint32_t tj[8][8], al[8];
+    if (live7)
+        load_row_tail<8, 0>(tab, c.ws.wsh + size_t(b) * L, L, pitch, i7, j0, jcol, c.ws.wabs[size_t(b) * L + i7],
+                            moff, tj, al);
+    auto partial = [&](int r, int cc, uint32_t Pi, uint32_t& cst, uint32_t& num) {
+        const double k = key[r][cc];
+        const double fl = floor(fmin(k, 0x1p33));
+        cst = k < 0x1p32 ? uint32_t(fl) - Pi : 0xffffffffu;
+        num = uint32_t((fmin(k, 0x1p33) - fl) * 256.0);
+    };
+#pragma unroll
+    for (int r = 0; r < 7; ++r) {
         const uint32_t Pi = P[i0 + r];
         const size_t row = chain + size_t(tri_row(L, i0 + r, j0)) * pitch + m;
 #pragma unroll
         for (int cc = 0; cc < 8; ++cc) {
-            if (j0 + cc < L) {
-                const double k = key[r][cc];
-                const double fl = floor(fmin(k, 0x1p33));
-                const uint32_t cst = k < 0x1p32 ? uint32_t(fl) - Pi : 0xffffffffu;
+            if (cc < cend) {
+                uint32_t cst, num;
+                partial(r, cc, Pi, cst, num);
                 c.cost[row + size_t(cc) * pitch] = int32_t(cst);
-                c.arg[row + size_t(cc) * pitch] = uint8_t(uint32_t((fmin(k, 0x1p33) - fl) * 256.0));
+                c.arg[row + size_t(cc) * pitch] = uint8_t(num);
+            }
+        }
+    }
+    if (live7) {
+        uint32_t best[8], pick[8];
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc) partial(7, cc, uint32_t(P[i7]), best[cc], pick[cc]);
+        finish_row<8, 0, 2>(c, chain, P, c.ws.mall + (size_t(b) * L + i7) * L, c.ws.mnull + (size_t(b) * L + i7) * L, L,
+                            pitch, i7, j0, cend, jcol, c.ws.fb[size_t(b) * L + i7], m, best, pick, tj, al);
+    } else {
+        const size_t row = chain + size_t(tri_row(L, i7, j0)) * pitch + m;
+#pragma unroll
+        for (int cc = 0; cc < 8; ++cc) {
+            if (cc < cend) {
+                c.cost[row + size_t(cc) * pitch] = int32_t(kInf);
+                c.arg[row + size_t(cc) * pitch] = 0;
             }
         }
     }
@@ -462,7 +561,7 @@ __global__ void __launch_bounds__(kRowWG) row_kernel(Ctx c, int D) {
     const uint32_t fbi = c.ws.fb[size_t(b) * L + i];
     const uint32_t wabi = c.ws.wabs[size_t(b) * L + i];
     const int rowi = tri_row(L, i, i) - i;  // + j = row of (i, j)
-    auto rowq = [&](int q) { return q * L - (q * (q - 1)) / 2 - q; };  // + j = row of (q, j)
+    auto rowq = [&](int q) { return row_base(L, q); };
 
     // Columns past the end of a ragged last block are computed on a clamped j and not stored.
     int jc[T];
@@ -512,25 +611,13 @@ __global__ void __launch_bounds__(kRowWG) row_kernel(Ctx c, int D) {
             pp[cc] = c.arg[o];
         }
     }
-    uint32_t tj[T][T];  // near-j: right (jb + c2 + 1, j) at its shift, for CF <= c2 < cc
-#pragma unroll
-    for (int cc = CF + 1; cc < T; ++cc)
-#pragma unroll
-        for (int c2 = CF; c2 < cc; ++c2) {
-            const int q = min(jb + c2 + 1, L - 1);
-            tj[c2][cc] = ld32(tab, uint32_t(rowq(q) + jc[cc]) * uint32_t(pitch) - uint32_t(wsh[q]), moff);
-        }
-    uint32_t al[T];  // C_all: right (i + 1, j) at m - omega_abar^{i+1}
-#pragma unroll
-    for (int cc = CF; cc < T; ++cc) {
-        const int i1 = min(i + 1, L - 1);
-        al[cc] = ld32(tab, uint32_t(rowq(i1) + max(jc[cc], i1)) * uint32_t(pitch) - wabi, moff);
-    }
+    uint32_t tj[T][T], al[T];
+    load_row_tail<T, CF>(tab, wsh, L, pitch, i, jb, jc, wabi, moff, tj, al);
 
     // ---- evaluation ----
-    uint32_t best[T], pick[T], val[T];
+    uint32_t best[T], pick[T];
 #pragma unroll
-    for (int cc = 0; cc < T; ++cc) best[cc] = 0xffffffffu, pick[cc] = 0, val[cc] = kInf;
+    for (int cc = 0; cc < T; ++cc) best[cc] = 0xffffffffu, pick[cc] = 0;
 #pragma unroll
     for (int u = 0; u < NQ; ++u) {
         const int q = i + 1 + u;
@@ -546,29 +633,7 @@ __global__ void __launch_bounds__(kRowWG) row_kernel(Ctx c, int D) {
         for (int cc = 0; cc < T; ++cc)
             if (pc[cc] < best[cc]) best[cc] = pc[cc], pick[cc] = pp[cc];
     }
-#pragma unroll
-    for (int cc = CF; cc < T; ++cc) {
-        const int j = jc[cc];
-#pragma unroll
-        for (int c2 = CF; c2 < cc; ++c2) {
-            const int q = min(jb + c2 + 1, L - 1);  // left operand (i, q-1) = val[c2]
-            const uint32_t v = val[c2] + (uint32_t(P[q]) - Pi) + tj[c2][cc];
-            if (v < best[cc]) best[cc] = v, pick[cc] = q + 1;
-        }
-        const uint32_t ck = (m >= uint32_t(mnull[j])) ? min(best[cc], kInf) : kInf;
-        uint32_t all = fbi;
-        if (DC != 0 || cc > CF) all += al[cc];  // j > i
-        all = (m >= uint32_t(mall[j])) ? min(all, kInf) : kInf;
-        const bool take_all = all < kInf && all <= ck;
-        const uint32_t fin = take_all ? all : ck;
-        const uint32_t fpk = take_all ? uint32_t(i + 1) : (ck < kInf ? pick[cc] : 0u);
-        val[cc] = fin;
-        if (cc < cend) {
-            const size_t o = chain + size_t(rowi + j) * pitch + m;
-            c.cost[o] = int32_t(fin);
-            c.arg[o] = uint8_t(fpk);
-        }
-    }
+    finish_row<T, CF, DC>(c, chain, P, mall, mnull, L, pitch, i, jb, cend, jc, fbi, m, best, pick, tj, al);
 }
 
 using RowFn = void (*)(Ctx, int);
@@ -910,9 +975,10 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
                                    dim3(64 * kCH), 0, gs[g], ctx, D);
                 CKPT_AFTER_LAUNCH(CKPT_K_GEMM);
             }
-            // rows of the two halves are issued alternately so that both queues stay fed
+            // rows of the two halves are issued alternately so that both queues stay fed; row 7 was
+            // finished by the gemm
             const auto& rowfn = kRow2;
-            for (int r = T - 1; r >= 0; --r) {
+            for (int r = T - 2; r >= 0; --r) {
                 for (int g = 0; g < groups; ++g) {
                     const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
                     hipLaunchKernelGGL(rowfn[r], dim3(gx_row, nblk - D, first[g + 1] - first[g]), dim3(kRowWG), 0,
