@@ -36,9 +36,10 @@
  *
  * Ownership and threading: every buffer belongs to the caller and must stay valid
  * until the work enqueued on the stream has finished.  The library's only state is the
- * last HIP error code and, per device, one helper stream with two events that
- * ckpt_solve_batched creates on its first call there and keeps (it runs half of a
- * batch on it, forked from and joined back into the caller's stream).  Calls from
+ * last HIP error code and, per device, three helper streams with four events that
+ * ckpt_solve_batched creates on its first large solve there and keeps (it runs up to
+ * three quarters of a batch on them, forked from and joined back into the caller's
+ * stream).  Calls from
  * several threads and on different streams with disjoint buffers are safe; their
  * enqueueing is serialised per device.
  *
@@ -113,7 +114,7 @@ size_t ckpt_workspace_bytes(int L, int M, int B);
  *             only; the arrays it names are read by the enqueued kernels)
  *   stream    a hipStream_t (NULL = the default stream); the call only enqueues
  *             work and returns, it does not synchronise and allocates no memory
- *             (see the helper stream above); it may be captured into a HIP graph
+ *             (see the helper streams above); it may be captured into a HIP graph
  *   cost, arg DEVICE tables laid out as above, 256-byte aligned
  *   workspace DEVICE memory of ckpt_workspace_bytes(L, M, B) bytes, 256-byte
  *             aligned; holds per-chain prefix sums, thresholds and input flags

@@ -10,6 +10,7 @@
 #include <utility>
 #include <cstdint>
 #include <cstring>
+#include <algorithm>
 #include <mutex>
 #include <type_traits>
 #include <vector>
@@ -872,11 +873,15 @@ struct Profile {
         if (prof && !prof->mark(kind)) return CKPT_E_HIP;         \
     } while (0)
 
-// Second stream of the two-way batch split, one per device, created on first use and kept
-// for the life of the process (default priority, non-blocking).
+// Streams of the batch split beside the caller's, per device, created on first use and kept
+// for the life of the process (default priority, non-blocking).  With the caller's stream they
+// make four, the number of hardware queues a process gets by default; more streams than that
+// share queues and serialise (measured: six or eight groups are slower than one).
+constexpr int kSideStreams = 3;
 struct Side {
-    hipStream_t stream = nullptr;
-    hipEvent_t fork = nullptr, join = nullptr;
+    hipStream_t stream[kSideStreams] = {};
+    hipEvent_t join[kSideStreams] = {};
+    hipEvent_t fork = nullptr;
     bool tried = false, ok = false;
     std::mutex busy;
 };
@@ -890,9 +895,10 @@ Side* side_streams() {
     std::lock_guard<std::mutex> guard(init);
     if (!s.tried) {
         s.tried = true;
-        s.ok = hip_ok(hipStreamCreateWithFlags(&s.stream, hipStreamNonBlocking)) &&
-               hip_ok(hipEventCreateWithFlags(&s.fork, hipEventDisableTiming)) &&
-               hip_ok(hipEventCreateWithFlags(&s.join, hipEventDisableTiming));
+        s.ok = hip_ok(hipEventCreateWithFlags(&s.fork, hipEventDisableTiming));
+        for (int k = 0; k < kSideStreams && s.ok; ++k)
+            s.ok = hip_ok(hipStreamCreateWithFlags(&s.stream[k], hipStreamNonBlocking)) &&
+                   hip_ok(hipEventCreateWithFlags(&s.join[k], hipEventDisableTiming));
     }
     return s.ok ? &s : nullptr;
 }
@@ -923,51 +929,55 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     const int nblk = (L + T - 1) / T;
     const int gx_gemm = (pitch / 64 + kCH - 1) / kCH, gx_row = (pitch + kRowWG - 1) / kRowWG;
 
-    // Two streams.  Chains are independent, so from D = 2 on the batch is split in two halves
-    // that run the same launch sequence on two streams: the many short row launches of one half
-    // overlap with work of the other half instead of leaving the machine idle between dependent
-    // launches.  Before that, the frontier (a few busy CUs for a long time) runs on the second
-    // stream next to the D = 0 and D = 1 rows of the whole batch, which do not need it.  The
-    // second stream is forked from and joined back into the caller's stream with events.
-    // Small problems are bound by launch latency, where a second stream only adds launches.
+    // Several streams.  Chains are independent, so from D = 2 on the batch is split in up to four
+    // groups that run the same launch sequence on as many streams: the many short row launches
+    // of one group overlap with work of the others instead of leaving the machine idle between
+    // dependent launches.  Before that, the frontier (a few busy CUs for a long time) runs on
+    // the first side stream next to the D = 0 and D = 1 rows of the whole batch, which do not
+    // need it.  The side streams are forked from and joined back into the caller's stream with
+    // events.  Small problems are bound by launch latency, where more streams only add launches.
     const bool split = !prof && B >= 2 && nblk >= 3 && size_t(B) * nblk * pitch >= (size_t(1) << 19);
     Side* side = split ? side_streams() : nullptr;
     std::unique_lock<std::mutex> lock;
     if (side) lock = std::unique_lock<std::mutex>(side->busy);  // one fork/join at a time per device
-    hipStream_t s2 = side ? side->stream : st;
+    const int groups = side ? std::min(B, kSideStreams + 1) : 1;
+    hipStream_t gs[kSideStreams + 1] = {st, st, st, st};  // stream of group g
+    for (int g = 1; g < groups; ++g) gs[g] = side->stream[g - 1];
+    int first[kSideStreams + 2];  // group g holds chains first[g] .. first[g + 1] - 1
+    for (int g = 0; g <= groups; ++g) first[g] = int((long long)B * g / groups);
 
-    bool forked = false;
+    int forked = 0;  // side streams that wait on the caller's stream and have to be joined back
+    auto join_side = [&](int k) {  // the caller's stream waits for side stream k
+        return hip_ok(hipEventRecord(side->join[k], side->stream[k])) &&
+               hip_ok(hipStreamWaitEvent(st, side->join[k], 0));
+    };
     auto enqueue = [&]() -> int {
         hipLaunchKernelGGL(precompute_kernel, dim3(B), dim3(256), 0, st, *chains, L, pitch, ws);
         CKPT_AFTER_LAUNCH(CKPT_K_PRECOMPUTE);
         if (side) {
-            if (!hip_ok(hipEventRecord(side->fork, st)) || !hip_ok(hipStreamWaitEvent(s2, side->fork, 0)))
+            if (!hip_ok(hipEventRecord(side->fork, st)) || !hip_ok(hipStreamWaitEvent(gs[1], side->fork, 0)))
                 return CKPT_E_HIP;
-            forked = true;
+            forked = 1;
         }
-        hipLaunchKernelGGL(frontier_kernel, dim3(B), dim3(1024), frontier_lds, s2, *chains, L, ws);
+        hipLaunchKernelGGL(frontier_kernel, dim3(B), dim3(1024), frontier_lds, gs[1], *chains, L, ws);
         CKPT_AFTER_LAUNCH(CKPT_K_FRONTIER);
 
-        auto launch_rows = [&](int D, int b0, int nb, hipStream_t s) -> int {
-            const Ctx ctx{L, M, pitch, rows, b0, ws, cost, arg};
-            const auto& rowfn = D == 0 ? kRow0 : (D == 1 ? kRow1 : kRow2);
+        for (int D = 0; D < 2 && D < nblk; ++D) {
+            const Ctx ctx{L, M, pitch, rows, 0, ws, cost, arg};
+            const auto& rowfn = D == 0 ? kRow0 : kRow1;
             for (int r = T - 1; r >= 0; --r) {
-                hipLaunchKernelGGL(rowfn[r], dim3(gx_row, nblk - D, nb), dim3(kRowWG), 0, s, ctx, D);
+                hipLaunchKernelGGL(rowfn[r], dim3(gx_row, nblk - D, B), dim3(kRowWG), 0, st, ctx, D);
                 CKPT_AFTER_LAUNCH(CKPT_K_ROW);
             }
-            return CKPT_OK;
-        };
-        for (int D = 0; D < 2 && D < nblk; ++D)
-            if (int rc = launch_rows(D, 0, B, st)) return rc;
-        if (side) {
-            // both streams wait for each other: the frontier is done, and so are the D < 2 rows
-            if (!hip_ok(hipEventRecord(side->join, s2)) || !hip_ok(hipStreamWaitEvent(st, side->join, 0)) ||
-                !hip_ok(hipEventRecord(side->fork, st)) || !hip_ok(hipStreamWaitEvent(s2, side->fork, 0)))
-                return CKPT_E_HIP;
         }
-        const int groups = side ? 2 : 1;
-        const int first[3] = {0, side ? B / 2 : B, B};
-        hipStream_t gs[2] = {st, s2};
+        if (side) {
+            // the caller's stream waits for the frontier, every side stream for the D < 2 rows
+            if (!join_side(0) || !hip_ok(hipEventRecord(side->fork, st))) return CKPT_E_HIP;
+            for (int g = 1; g < groups; ++g) {
+                if (!hip_ok(hipStreamWaitEvent(gs[g], side->fork, 0))) return CKPT_E_HIP;
+                forked = g;
+            }
+        }
         for (int D = 2; D < nblk; ++D) {
             for (int g = 0; g < groups; ++g) {
                 const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
@@ -975,13 +985,12 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
                                    dim3(64 * kCH), 0, gs[g], ctx, D);
                 CKPT_AFTER_LAUNCH(CKPT_K_GEMM);
             }
-            // rows of the two halves are issued alternately so that both queues stay fed; row 7 was
+            // rows of the groups are issued in turn so that every queue stays fed; row 7 was
             // finished by the gemm
-            const auto& rowfn = kRow2;
             for (int r = T - 2; r >= 0; --r) {
                 for (int g = 0; g < groups; ++g) {
                     const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
-                    hipLaunchKernelGGL(rowfn[r], dim3(gx_row, nblk - D, first[g + 1] - first[g]), dim3(kRowWG), 0,
+                    hipLaunchKernelGGL(kRow2[r], dim3(gx_row, nblk - D, first[g + 1] - first[g]), dim3(kRowWG), 0,
                                        gs[g], ctx, D);
                     CKPT_AFTER_LAUNCH(CKPT_K_ROW);
                 }
@@ -989,11 +998,11 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
         }
         return CKPT_OK;
     };
-    const int rc = enqueue();
-    // The second stream always rejoins the caller's stream, also after a failed launch, so that
+    int rc = enqueue();
+    // Every forked side stream rejoins the caller's stream, also after a failed launch, so that
     // the caller's stream (or a capture in progress) is never left with an open fork.
-    if (forked && (!hip_ok(hipEventRecord(side->join, s2)) || !hip_ok(hipStreamWaitEvent(st, side->join, 0))))
-        return rc ? rc : CKPT_E_HIP;
+    for (int k = 0; k < forked; ++k)
+        if (!join_side(k) && rc == CKPT_OK) rc = CKPT_E_HIP;
     return rc;
 }
 

@@ -66,7 +66,8 @@ def test_random_shapes(amd, oracle_mod, seed):
 @pytest.mark.parametrize("L,M,B,seed,size_hi", [
     (6, 70000, 2, 31, 9000),      # rows much wider than any tile of m
     (20, 20000, 1, 32, 1500),
-    (40, 36000, 3, 33, 1200),     # large enough for the two-stream schedule, odd batch split
+    (40, 36000, 3, 33, 1200),     # large enough for the multi-stream schedule: three groups of one chain
+    (32, 30000, 5, 35, 1000),     # four groups of 1, 1, 1 and 2 chains
     (10, 100, 700, 34, 9),        # more chains than threads of any block
 ])
 def test_wide_rows_and_many_chains(amd, oracle_mod, L, M, B, seed, size_hi):
