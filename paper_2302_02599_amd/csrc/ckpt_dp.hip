@@ -356,8 +356,10 @@ __device__ __forceinline__ void finish_row(const Ctx& c, size_t chain, const int
 // Output, rows 0..6 of the tile: cost[] <- unsaturated partial minimum (0xffffffff if none),
 // arg[] <- its number; row_kernel finishes them.  Row 7 has no split in its own row block, so
 // its partial minimum stays in registers and the wave finishes the row itself.
-template <int NB, int UNR, int CH>
-__global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
+// KS > 1 (launches with too few tiles to fill the chip): KS waves share one chunk, each takes
+// every KS-th entry of the work list, and their key tiles are merged through LDS at the end.
+template <int NB, int UNR, int CH, int KS>
+__global__ void __launch_bounds__(64 * CH * KS, 2) gemm_kernel(Ctx c, int D) {
     constexpr int T = kT;
     static_assert(T == 8, "one wave per 8x8 tile");
     const Work w = work_of_block();
@@ -368,7 +370,8 @@ __global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(int(threadIdx.x >> 6));
     const int bx = w.chunk;
-    const int chunk = bx * CH + wave;  // this wave's 64 columns of m
+    const int cw = wave / KS, slice = wave % KS;  // chunk within the work-group, slice of the list
+    const int chunk = bx * CH + cw;  // this wave's 64 columns of m
     const uint32_t m = chunk * 64 + lane;
     const int m_hi = min((bx * CH + CH) * 64, pitch) - 1;  // largest m of the work-group
     const uint32_t moff = m * 4;
@@ -421,8 +424,11 @@ __global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
         if (lane == 0) s_n = n;
     }
     __syncthreads();
-    const int n = s_n;
-    if (chunk * 64 >= pitch) return;
+    const bool active = chunk * 64 < pitch;
+    if (KS == 1 && !active) return;  // KS > 1: every wave stays for the barriers of the merge
+    // this wave's entries: slice, slice + KS, ...
+    const int n = active && s_n > slice ? (s_n - slice + KS - 1) / KS : 0;
+    auto entry = [&](int t) { return slice + KS * t; };
 
     double key[8][8];
 #pragma unroll
@@ -432,7 +438,8 @@ __global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
 
     if (n > 0) {
         uint32_t buf[NB][16];
-        auto load = [&](uint32_t(&v)[16], int k) {
+        auto load = [&](uint32_t(&v)[16], int t) {
+            const int k = entry(t);
             const int q = __builtin_amdgcn_readfirstlane(s_q[k]);
             const int sh = __builtin_amdgcn_readfirstlane(s_sh[k]);
             const int rq = q * L - (q * (q - 1)) / 2 - q;  // + j = row of (q, j)
@@ -442,8 +449,8 @@ __global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
             for (int cc = 0; cc < 8; ++cc)
                 v[8 + cc] = ld32(tab, uint32_t(rq + jcol[cc]) * uint32_t(pitch) - uint32_t(sh), moff);
         };
-        auto compute = [&](const uint32_t(&v)[16], int k) {
-            const double cq = s_kq[k];
+        auto compute = [&](const uint32_t(&v)[16], int t) {
+            const double cq = s_kq[entry(t)];
             double lk[8], rk[8];
 #pragma unroll
             for (int r = 0; r < 8; ++r) lk[r] = double(v[r]);
@@ -477,6 +484,28 @@ __global__ void __launch_bounds__(64 * CH, 2) gemm_kernel(Ctx c, int D) {
         const int bulk = n / STEPS, tail = (n - bulk * STEPS + NB - 1) / NB;
         for (int it = 0; it < bulk; ++it) steps(std::integral_constant<int, STEPS>{}, k);
         for (int it = 0; it < tail; ++it) steps(std::integral_constant<int, NB>{}, k);
+    }
+
+    if constexpr (KS > 1) {
+        // Merge: row by row of the tile, the waves of slices 1.. hand their keys to the wave of
+        // slice 0 through LDS.  Every wave of the work-group passes all sixteen barriers.
+        __shared__ double s_red[CH][KS - 1][8][64];
+#pragma unroll
+        for (int r = 0; r < 8; ++r) {
+            if (slice > 0) {
+#pragma unroll
+                for (int cc = 0; cc < 8; ++cc) s_red[cw][slice - 1][cc][lane] = key[r][cc];
+            }
+            __syncthreads();
+            if (slice == 0) {
+#pragma unroll
+                for (int o = 0; o < KS - 1; ++o)
+#pragma unroll
+                    for (int cc = 0; cc < 8; ++cc) key[r][cc] = fmin(key[r][cc], s_red[cw][o][cc][lane]);
+            }
+            __syncthreads();
+        }
+        if (slice != 0 || !active) return;
     }
 
     const int32_t* P = c.ws.P + size_t(b) * (L + 1);
@@ -927,7 +956,7 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     }
     constexpr int T = kT;
     const int nblk = (L + T - 1) / T;
-    const int gx_gemm = (pitch / 64 + kCH - 1) / kCH, gx_row = (pitch + kRowWG - 1) / kRowWG;
+    const int gx_row = (pitch + kRowWG - 1) / kRowWG;
 
     // Several streams.  Chains are independent, so from D = 2 on the batch is split in up to four
     // groups that run the same launch sequence on as many streams: the many short row launches
@@ -979,10 +1008,20 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
             }
         }
         for (int D = 2; D < nblk; ++D) {
+            // The last diagonals have few tiles: when all groups together bring fewer waves than
+            // the chip holds, 2 or 4 waves share each chunk and split its work list.
+            const long long waves = (long long)(nblk - D) * (pitch / 64) * B;
+            const int ks = waves <= 600 ? 4 : (waves <= 1700 ? 2 : 1);
+            const int gx = (pitch / 64 + kCH / ks - 1) / (kCH / ks);
             for (int g = 0; g < groups; ++g) {
                 const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
-                hipLaunchKernelGGL((gemm_kernel<3, 3, kCH>), dim3(gx_gemm, nblk - D, first[g + 1] - first[g]),
-                                   dim3(64 * kCH), 0, gs[g], ctx, D);
+                const dim3 grid(gx, nblk - D, first[g + 1] - first[g]), block(64 * kCH);
+                if (ks == 4)
+                    hipLaunchKernelGGL((gemm_kernel<3, 3, kCH / 4, 4>), grid, block, 0, gs[g], ctx, D);
+                else if (ks == 2)
+                    hipLaunchKernelGGL((gemm_kernel<3, 3, kCH / 2, 2>), grid, block, 0, gs[g], ctx, D);
+                else
+                    hipLaunchKernelGGL((gemm_kernel<3, 3, kCH, 1>), grid, block, 0, gs[g], ctx, D);
                 CKPT_AFTER_LAUNCH(CKPT_K_GEMM);
             }
             // rows of the groups are issued in turn so that every queue stays fed; row 7 was
