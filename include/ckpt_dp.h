@@ -39,9 +39,8 @@
  * last HIP error code and, per device, three helper streams with four events that
  * ckpt_solve_batched creates on its first large solve there and keeps (it runs up to
  * three quarters of a batch on them, forked from and joined back into the caller's
- * stream).  Calls from
- * several threads and on different streams with disjoint buffers are safe; their
- * enqueueing is serialised per device.
+ * stream).  Calls from several threads and on different streams with disjoint
+ * buffers are safe; their enqueueing is serialised per device.
  *
  * Errors: every function that can fail returns CKPT_OK (0) or a negative code and
  * never throws or aborts.  Argument errors are reported before anything is
