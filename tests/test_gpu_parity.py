@@ -166,14 +166,18 @@ def test_solve_on_a_side_stream(amd, oracle_mod):
     assert_tables_equal(oracle_mod, batch, sol)
 
 
-def test_solve_can_be_captured_in_a_hip_graph(amd):
-    """Capture one solve (including the internal fork/join onto the second stream), replay it several
-    times with eager work and synchronisations in between, and compare every replay with the eager tables."""
+@pytest.mark.parametrize("which", ["one_stream", "four_streams"])
+def test_solve_can_be_captured_in_a_hip_graph(amd, which):
+    """Capture one solve, replay it several times with eager work and synchronisations in between,
+    and compare every replay with the eager tables.  The larger batch is split over the library's
+    side streams, so its capture includes their fork and join."""
     import torch
-    batch = make_config(2)
+    batch = make_config(2) if which == "one_stream" else \
+        random_chain_batch(32, 30000, 5, 36, size_hi=1000, time_hi=5000, overheads=True)
     L, M, B = batch.L, batch.M, batch.B
-    up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
     uf, ub, wa, wabar = up(batch.uf), up(batch.ub), up(batch.wa), up(batch.wabar)
+    opt = dict(wdelta=up(batch.wdelta), of=up(batch.of), ob=up(batch.ob))
     cost = torch.empty(amd.ckpt_table_elems(L, M, B), dtype=torch.int32, device="cuda")
     arg = torch.empty(amd.ckpt_table_elems(L, M, B), dtype=torch.uint8, device="cuda")
     ws = torch.empty(amd.ckpt_workspace_bytes(L, M, B), dtype=torch.uint8, device="cuda")
@@ -181,11 +185,11 @@ def test_solve_can_be_captured_in_a_hip_graph(amd):
     torch.cuda.synchronize()
     side = torch.cuda.Stream()
     with torch.cuda.stream(side):
-        amd.ckpt_solve_batched(uf, ub, wa, wabar, L, M, B, cost, arg, ws)      # warm-up outside the capture
+        amd.ckpt_solve_batched(uf, ub, wa, wabar, L, M, B, cost, arg, ws, **opt)      # warm-up outside the capture
     torch.cuda.synchronize()
     graph = torch.cuda.CUDAGraph()
     with torch.cuda.graph(graph, stream=side):
-        amd.ckpt_solve_batched(uf, ub, wa, wabar, L, M, B, cost, arg, ws)
+        amd.ckpt_solve_batched(uf, ub, wa, wabar, L, M, B, cost, arg, ws, **opt)
     torch.cuda.synchronize()
     pitch = amd.ckpt_row_pitch(M)
     for _ in range(3):
@@ -198,10 +202,16 @@ def test_solve_can_be_captured_in_a_hip_graph(amd):
         assert (arg.view(B, -1, pitch)[:, :, :M + 1] == eager.arg[:, :, :M + 1]).all()
 
 
-def test_concurrent_solves_on_two_streams(amd, oracle_mod):
-    """Two solves in flight at once on different caller streams share the library's second stream."""
+@pytest.mark.parametrize("which", ["small", "split"])
+def test_concurrent_solves_on_two_streams(amd, oracle_mod, which):
+    """Two solves in flight at once on different caller streams; the larger ones both use the
+    library's side streams."""
     import torch
-    b1, b2 = make_config(2), random_chain_batch(40, 300, 4, 33, size_hi=9, overheads=True)
+    if which == "small":
+        b1, b2 = make_config(2), random_chain_batch(40, 300, 4, 33, size_hi=9, overheads=True)
+    else:
+        b1 = random_chain_batch(48, 16000, 16, 37, size_hi=600, time_hi=3000)
+        b2 = random_chain_batch(32, 30000, 5, 38, size_hi=1000, time_hi=5000, overheads=True)
     s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
     with torch.cuda.stream(s1):
         sol1 = amd.solve(b1, check=False)
@@ -209,7 +219,7 @@ def test_concurrent_solves_on_two_streams(amd, oracle_mod):
         sol2 = amd.solve(b2, check=False)
     torch.cuda.synchronize()
     assert_tables_equal(oracle_mod, b1, sol1, nthreads=8, chains=[0, 7, 15])
-    assert_tables_equal(oracle_mod, b2, sol2, nthreads=4)
+    assert_tables_equal(oracle_mod, b2, sol2, nthreads=8)
 
 
 def _full_solution(amd, cfg):
