@@ -269,10 +269,10 @@ int ckpt_simulate_batched(const ckpt_chains_t* chains, int L, int B, const ckpt_
  *   group_of_node[n]               HOST out: group index 0.., -1 for placeholders
  *   is_common[n]                   HOST out: 1 if the node is a common node (seeded, or its
  *                                  operation is non-differentiable, or all its parents are common)
- * A node ends a group when, after releasing one dependency of each of its parents that is
- * neither placeholder nor common, no dependency is pending and none of its children is an
- * in-place or communication operation; a node that is not common then registers one
- * dependency per non-placeholder child.  Nodes left after the last cut form a final group.
+ * A node that is neither placeholder nor common keeps dependencies outstanding until the last
+ * of its non-placeholder children has been appended.  A node ends a group when, once it has
+ * been appended, no earlier node has a dependency outstanding and none of its own children is
+ * an in-place or communication operation.  Nodes left after the last cut form a final group.
  * Returns the number of groups, or CKPT_E_ARG (bad pointers, edges that are not forward).
  */
 enum {

@@ -290,57 +290,54 @@ PLACEHOLDER, COMMON_SEED, NON_DIFF, IN_PLACE, COMM = 1, 2, 4, 8, 16
 
 
 def linearize(children, flags):
-    """Network linearisation, Algorithm "network linearization algorithm" with the definitions of
-    Sections "Linearization" and "Common Node".
+    """Network linearisation: the node groups that become the stages of a chain, written from the
+    definitions of Sections "Linearization", "Common Node" and "Full Set of Linearization Rules".
 
     Nodes 0..n-1 are in topological order; children[v] lists the children of v; flags[v] is a
-    bit set of PLACEHOLDER (network input/output), COMMON_SEED (a non-differentiable input such
-    as an attention mask), NON_DIFF (non-differentiable operation such as getattr/getitem),
-    IN_PLACE, COMM (communication operation).
+    bit set of PLACEHOLDER (network input/output, never examined), COMMON_SEED (a
+    non-differentiable input such as an attention mask), NON_DIFF (non-differentiable operation
+    such as getattr/getitem), IN_PLACE, COMM (communication operation).
 
-    Steps, in the paper's order, for every node that is not a placeholder: release one
-    dependency of each parent that is neither a placeholder nor a common node; append the node
-    to the current group; if the pool of pending dependencies is empty and no child of the node
-    is an in-place or communication operation, close the group; then either label the node
-    common (its operation is non-differentiable, or all of its parents are common) or put its
-    own dependencies (one per child that will be examined, i.e. not a placeholder) in the pool.
+    Common nodes (definition and lemma of "Common Node"): a seeded node; an examined node whose
+    operation is non-differentiable; an examined node all of whose parents are common (a node
+    without parents counts as such).  Common nodes and placeholders hold no dependencies.
+
+    End of a node group (basic rule of "Linearization" plus the two sticking rules): examined
+    node v ends a group exactly when
+      (a) no dependency is outstanding once v has been appended, i.e. no edge u -> c runs from
+          an examined, non-common node u before v to an examined node c after v, and
+      (b) no child of v is an in-place or a communication operation (such children stay in the
+          group of their parent).
+    Groups are the runs of examined nodes up to and including each end; nodes after the last end
+    form a final group.
 
     Returns (group index per node, -1 for placeholders; common flag per node; number of groups).
-    Nodes left over after the last closed group form a final group.
     """
     n = len(children)
-    parents = [[] for _ in range(n)]
-    for v in range(n):
-        for c in children[v]:
-            parents[c].append(v)
-    common = [bool(flags[v] & COMMON_SEED) for v in range(n)]
-    pool = {}
+    examined = [not (flags[v] & PLACEHOLDER) for v in range(n)]
+    parents = [[u for u in range(n) if v in children[u]] for v in range(n)]
+    common = [False] * n
+    for v in range(n):      # parents come first in a topological order
+        common[v] = bool(flags[v] & COMMON_SEED) or (
+            examined[v] and (bool(flags[v] & NON_DIFF) or all(common[p] for p in parents[v])))
+
+    def outstanding(v):
+        return any(examined[u] and not common[u] and examined[c] and c > v
+                   for u in range(v) for c in children[u])
+
+    def sticks(v):
+        return any(flags[c] & (IN_PLACE | COMM) for c in children[v])
+
     group = [-1] * n
-    current = []
-    ngroups = 0
+    ngroups, open_group = 0, False
     for v in range(n):
-        if flags[v] & PLACEHOLDER:
+        if not examined[v]:
             continue
-        for p in parents[v]:
-            if not (flags[p] & PLACEHOLDER) and not common[p]:
-                pool[p] -= 1
-                if pool[p] == 0:
-                    del pool[p]
-        current.append(v)
-        sticky = any(flags[c] & (IN_PLACE | COMM) for c in children[v])
-        if not pool and not sticky:
-            for u in current:
-                group[u] = ngroups
+        group[v] = ngroups
+        open_group = True
+        if not outstanding(v) and not sticks(v):
             ngroups += 1
-            current = []
-        if (flags[v] & NON_DIFF) or all(common[p] for p in parents[v]):
-            common[v] = True
-        else:
-            deps = sum(1 for c in children[v] if not flags[c] & PLACEHOLDER)
-            if deps:
-                pool[v] = deps
-    if current:
-        for u in current:
-            group[u] = ngroups
+            open_group = False
+    if open_group:
         ngroups += 1
     return group, common, ngroups

@@ -16,54 +16,40 @@ extern "C" int ckpt_linearize(int n, const int32_t* child_ptr, const int32_t* ch
         for (int e = child_ptr[v]; e < child_ptr[v + 1]; ++e)
             if (child_idx[e] <= v || child_idx[e] >= n) return CKPT_E_ARG;  // not a topological order
     }
-    // One pass in node order.  pending[v] = dependencies of v not yet released; open = number
-    // of nodes with pending > 0 (the "pool" is empty iff open == 0).
-    std::vector<int32_t> pending(n, 0);
-    std::vector<uint8_t> tracked(n, 0);
-    int open = 0, groups = 0;
-    for (int v = 0; v < n; ++v) is_common[v] = (flags[v] & CKPT_NODE_COMMON_SEED) ? 1 : 0;
-    // the release step walks a node's parents: build the reverse adjacency once
-    std::vector<int32_t> par_ptr(n + 1, 0);
-    for (int e = 0; e < child_ptr[n]; ++e) ++par_ptr[child_idx[e] + 1];
-    for (int v = 0; v < n; ++v) par_ptr[v + 1] += par_ptr[v];
-    std::vector<int32_t> par_idx(child_ptr[n]), fill(par_ptr.begin(), par_ptr.end() - 1);
-    for (int v = 0; v < n; ++v)
-        for (int e = child_ptr[v]; e < child_ptr[v + 1]; ++e) par_idx[fill[child_idx[e]]++] = v;
-
-    for (int v = 0; v < n; ++v) group_of_node[v] = -1;
-    std::vector<int32_t> current;
+    // One forward sweep over the CSR adjacency, no reverse edges and no dependency pool:
+    //   - a node is common when it is seeded, non-differentiable, or has no non-common parent;
+    //     every non-common node (placeholders included) counts itself into its children;
+    //   - an examined, non-common node keeps dependencies outstanding until its last examined
+    //     child has been appended, so "no dependency outstanding after v" is a running maximum
+    //     of those last uses (horizon) that does not pass v.
+    std::vector<int32_t> noncommon_parents(n, 0);
+    int groups = 0;
+    int32_t horizon = -1;
+    bool open_group = false;
     for (int v = 0; v < n; ++v) {
-        if (flags[v] & CKPT_NODE_PLACEHOLDER) continue;
-        bool parents_common = true;
-        for (int e = par_ptr[v]; e < par_ptr[v + 1]; ++e) {
-            const int p = par_idx[e];
-            if (!is_common[p]) parents_common = false;
-            if (tracked[p] && --pending[p] == 0) --open;
-        }
-        current.push_back(v);
+        const bool placeholder = flags[v] & CKPT_NODE_PLACEHOLDER;
+        const bool common = (flags[v] & CKPT_NODE_COMMON_SEED) ||
+                            (!placeholder && ((flags[v] & CKPT_NODE_NON_DIFF) || noncommon_parents[v] == 0));
+        is_common[v] = common ? 1 : 0;
         bool sticky = false;
-        int deps = 0;
+        int32_t last_use = -1;
         for (int e = child_ptr[v]; e < child_ptr[v + 1]; ++e) {
-            const uint8_t cf = flags[child_idx[e]];
-            if (cf & (CKPT_NODE_IN_PLACE | CKPT_NODE_COMM)) sticky = true;
-            if (!(cf & CKPT_NODE_PLACEHOLDER)) ++deps;
+            const int c = child_idx[e];
+            if (!common) ++noncommon_parents[c];
+            if (flags[c] & (CKPT_NODE_IN_PLACE | CKPT_NODE_COMM)) sticky = true;
+            if (!(flags[c] & CKPT_NODE_PLACEHOLDER) && c > last_use) last_use = c;
         }
-        if (open == 0 && !sticky) {
-            for (int u : current) group_of_node[u] = groups;
+        if (placeholder) {
+            group_of_node[v] = -1;
+            continue;
+        }
+        group_of_node[v] = groups;
+        open_group = true;
+        if (horizon <= v && !sticky) {  // nothing outstanding, no child that sticks to v: v ends its group
             ++groups;
-            current.clear();
+            open_group = false;
         }
-        if ((flags[v] & CKPT_NODE_NON_DIFF) || parents_common) {
-            is_common[v] = 1;
-        } else if (deps > 0) {
-            tracked[v] = 1;
-            pending[v] = deps;
-            ++open;
-        }
+        if (!common && last_use > horizon) horizon = last_use;
     }
-    if (!current.empty()) {
-        for (int u : current) group_of_node[u] = groups;
-        ++groups;
-    }
-    return groups;
+    return groups + (open_group ? 1 : 0);
 }

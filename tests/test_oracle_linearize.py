@@ -1,4 +1,6 @@
-"""Pins of the oracle's network linearisation (Algorithm "network linearization algorithm")."""
+"""Pins of the oracle's network linearisation (Sections "Linearization", "Common Node", "Full Set of
+Linearization Rules"): three graphs cut by hand, and on random DAGs a last-use sweep and the
+common-node lemma as a fixed point, both written differently from the oracle."""
 import random
 
 import pytest
@@ -6,21 +8,21 @@ import pytest
 P, SEED, NOND, INPL, COMM = 1, 2, 4, 8, 16
 
 
-def _cut_positions_by_definition(children, flags, common):
-    """Independent statement of where groups end (Section "Linearization": a node ends a group when,
-    after its parents' dependencies are removed, no dependency is left): position v is a cut iff no
-    edge u -> c with u < v < c exists for an examined, non-common u and an examined c, and no
-    child of v is an in-place or communication operation.  Direct scan over edges, no running pool."""
+def _cuts_by_last_use(children, flags, common):
+    """Where groups end, stated differently from the oracle (which scans edges per node): every
+    examined, non-common node holds its dependencies until its LAST examined child has been
+    appended, so the pool is empty after position v iff the running maximum of those last uses
+    over the nodes before v does not pass v.  One forward sweep with a running maximum."""
     n = len(children)
-    cuts = []
+    cuts, horizon = [], -1          # horizon: latest position at which a dependency of an earlier node ends
     for v in range(n):
         if flags[v] & P:
             continue
-        crossing = any(c > v for u in range(v) if not flags[u] & P and not common[u]
-                       for c in children[u] if not flags[c] & P)
         sticky = any(flags[c] & (INPL | COMM) for c in children[v])
-        if not crossing and not sticky:
+        if horizon <= v and not sticky:
             cuts.append(v)
+        if not common[v]:
+            horizon = max([horizon] + [c for c in children[v] if not flags[c] & P])
     return cuts
 
 
@@ -94,7 +96,7 @@ def test_random_dags_against_the_definition(oracle_mod, seed):
     group, common, ngroups = oracle_mod.linearize(children, flags)
     assert common == [c and not (flags[v] & P and not flags[v] & SEED) for v, c in
                       enumerate(_common_by_fixpoint(children, flags))]
-    cuts = _cut_positions_by_definition(children, flags, common)
+    cuts = _cuts_by_last_use(children, flags, common)
     examined = [v for v in range(n) if not flags[v] & P]
     want, g = {}, 0
     for v in examined:
