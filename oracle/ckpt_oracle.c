@@ -28,14 +28,18 @@
  * Parity pins (tests/test_oracle_*.py): hand-derived L=3 example, brute force
  * over every persistent schedule for L <= 6 through an independent operation
  * simulator, the unlimited-memory closed form, monotonicity in m, the
- * infeasibility bound, an independent scalar minimum-memory recursion.
+ * infeasibility bound, an independent scalar minimum-memory recursion.  The
+ * m_null gate, which no schedule-level check can see when every omega_abar is
+ * at least its omega_a (it is then implied by the feasibility of the
+ * operands), is pinned by the peak of the forward sweep F_ck^s,
+ * F_null^{s+1..t-1} run through that same simulator.
  *
- * Parity unpinned: (i) the m_null gate of the checkpoint branch -- when every
- * omega_abar is at least its omega_a the gate is implied by the feasibility of
- * the operands, so no schedule-level check can see it; it is only compared with
- * the peak of the simulated forward sweep.  (ii) Inputs with an omega_abar
- * below its omega_a: the table follows the printed formulas and is compared
- * only with a second, separately written evaluation of those formulas.
+ * Outside the model: an omega_abar below its omega_a contradicts the paper's
+ * "abar contains a"; the Theorem is then no longer the optimum over
+ * persistent schedules (the brute force shows counter-examples), so there is
+ * nothing to be exact against.  The functions below still evaluate the printed
+ * formulas on such inputs; the GPU library flags them as a violated
+ * precondition.
  */
 #include <stdint.h>
 #include <stdlib.h>

@@ -125,6 +125,42 @@ def reconstruct(choice, wa, wabar, s, t, m):
     return ops
 
 
+def block_indices(ops, L):
+    """Activation-checkpoint block index of every stage (Section "Code generation": each node is
+    annotated with the index of its checkpoint block, nodes with the same index are packaged
+    into one function that is wrapped in the framework's checkpoint call, which keeps the
+    block's input and recomputes its inside during the backward phase).
+
+    Read off an operation list of Table 1 over stages 1..L.  A stage's annotation comes from the
+    FIRST forward operation it receives (its later forwards are the recomputation itself):
+      F_all^j   keeps abar^j: stage j lies in no checkpoint block, index -1;
+      F_ck^j    keeps only the input a^{j-1} and the output a^j: stage j opens a new block;
+      F_null^j  keeps nothing of its own: stage j continues the block of stage j-1.
+    Blocks are numbered 0, 1, ... in chain order.  Returns (list of L indices, number of blocks).
+    Raises ValueError if some stage has no forward operation, or if a first F_null^j does not
+    follow a stage that is inside a block.
+    """
+    first = {}
+    for kind, j in ops:
+        kind, j = int(kind), int(j)
+        if kind in (F_ALL, F_CK, F_NULL) and j not in first:
+            first[j] = kind
+    block, nblocks = [], 0
+    for j in range(1, L + 1):
+        if j not in first:
+            raise ValueError(f"stage {j} is never run forward")
+        if first[j] == F_ALL:
+            block.append(-1)
+        elif first[j] == F_CK:
+            block.append(nblocks)
+            nblocks += 1
+        else:
+            if j == 1 or block[-1] < 0:
+                raise ValueError(f"F_null^{j} does not continue a checkpoint block")
+            block.append(block[-1])
+    return block, nblocks
+
+
 def simulate(ops, L, uf, ub, wa, wabar, wdelta=None, of=None, ob=None):
     """Run an operation list over the whole chain 1..L and return (time, peak memory).
 

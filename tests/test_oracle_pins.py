@@ -8,7 +8,7 @@ import os
 import numpy as np
 import pytest
 
-from persistent_bruteforce import (BWD, F_ALL, brute_force_segment, flatten, simulate, trees)
+from persistent_bruteforce import (BWD, F_ALL, F_CK, F_NULL, brute_force_segment, flatten, simulate, trees)
 from workloads import make_config, random_chain_batch
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
@@ -153,23 +153,23 @@ def test_single_stage(oracle_mod):
 
 
 def test_thresholds_match_simulated_peaks(oracle_mod):
-    """m_all^{s,s} is the simulated peak of F_all^s, B^s; m_null^{s,t} is the simulated
-    peak of the forward sweep F_ck^s, F_null^{s+1..t-1} with delta^t resident."""
-    batch = random_chain_batch(7, 10, 1, 5, size_hi=9, overheads=True, own_wdelta=True)
-    uf, ub, wa, wabar, wd, of, ob = batch.chain(0)
-    L = batch.L
-    for s in range(1, L + 1):
-        m_all, _ = oracle_mod.thresholds(L, wa, wabar, wd, of, ob, s, s)
-        _, peak = simulate([(F_ALL, s), (BWD, s)], s, s, uf, ub, wa, wabar, wd, of, ob)
-        assert m_all == peak
-        for t in range(s + 1, L + 1):
-            _, m_null = oracle_mod.thresholds(L, wa, wabar, wd, of, ob, s, t)
-            # forward sweep only: simulate by hand with the simulator's own accounting
-            resident = int(wd[t])
-            peak = resident + int(wa[s]) + int(of[s - 1])
-            for j in range(s + 1, t):
-                peak = max(peak, resident + int(wa[j - 1]) + int(wa[j]) + int(of[j - 1]))
-            assert m_null == peak
+    """m_all^{s,s} is the simulated peak of F_all^s, B^s; m_null^{s,t} is the simulated peak of
+    the forward sweep F_ck^s, F_null^{s+1..t-1} run as a prefix of a schedule of s..t (delta^t
+    resident, segment input free) through the set-based simulator, which knows only Table 1."""
+    for seed, ovh, wd_own in [(5, True, True), (6, False, False), (7, True, False), (8, False, True)]:
+        batch = random_chain_batch(7, 10, 2, seed, size_hi=9, overheads=ovh, own_wdelta=wd_own)
+        for b in range(batch.B):
+            uf, ub, wa, wabar, wd, of, ob = batch.chain(b)
+            L = batch.L
+            for s in range(1, L + 1):
+                m_all, _ = oracle_mod.thresholds(L, wa, wabar, wd, of, ob, s, s)
+                _, peak = simulate([(F_ALL, s), (BWD, s)], s, s, uf, ub, wa, wabar, wd, of, ob)
+                assert m_all == peak
+                for t in range(s + 1, L + 1):
+                    _, m_null = oracle_mod.thresholds(L, wa, wabar, wd, of, ob, s, t)
+                    sweep = [(F_CK, s)] + [(F_NULL, j) for j in range(s + 1, t)]
+                    _, peak = simulate(sweep, s, t, uf, ub, wa, wabar, wd, of, ob, complete=False)
+                    assert m_null == peak, (s, t)
 
 
 @pytest.mark.parametrize("cfg", [0, 1])

@@ -8,7 +8,7 @@ must disagree with the brute force over persistent schedules.
 import numpy as np
 import pytest
 
-from persistent_bruteforce import brute_force_segment
+from persistent_bruteforce import F_CK, F_NULL, brute_force_segment, simulate
 from workloads import make_config, random_chain_batch
 
 INF = 1 << 30
@@ -115,6 +115,57 @@ def test_m_null_gate_is_implied_when_abar_contains_a():
         assert py_table(L, M, *ch, mistake="no_m_null_gate") == py_table(L, M, *ch)
 
 
+def _m_null(wa, wd, of, s, t, mistake=None):
+    """The Theorem's m_null^{s,t}, with one planted mistake at a time."""
+    lo, hi = s + 1, t                    # inner maximum over lo <= j < hi
+    if mistake == "sweep_stops_one_stage_early":
+        hi = t - 1
+    if mistake == "sweep_includes_stage_t":
+        hi = t + 1
+    first = wa[s] + of[s - 1]
+    if mistake == "first_forward_without_overhead":
+        first = wa[s]
+    inner = [wa[j - 1] + wa[j] + of[j - 1] for j in range(lo, min(hi, len(wa)))]
+    if mistake == "input_of_f_null_not_counted":
+        inner = [wa[j] + of[j - 1] for j in range(lo, hi)]
+    if mistake == "overhead_of_the_wrong_stage":
+        inner = [wa[j - 1] + wa[j] + of[j - 2] for j in range(lo, hi)]
+    total = wd[t] + max([first] + inner)
+    if mistake == "delta_of_the_segment_end_forgotten":
+        total -= wd[t]
+    if mistake == "delta_of_the_wrong_end":
+        total += wd[s - 1] - wd[t]
+    return total
+
+
+M_NULL_MISTAKES = ["sweep_stops_one_stage_early", "sweep_includes_stage_t", "first_forward_without_overhead",
+                   "input_of_f_null_not_counted", "overhead_of_the_wrong_stage",
+                   "delta_of_the_segment_end_forgotten", "delta_of_the_wrong_end"]
+
+
+def _m_null_disagrees_with_simulated_sweep(mistake):
+    """m_null is not visible to the brute force (see the test above); its pin is the peak of the
+    forward sweep F_ck^s, F_null^{s+1..t-1} in the set-based simulator, delta^t resident."""
+    for L, _, ch in _cases():
+        uf, ub, wa, wabar, wd, of, ob = ch
+        for s in range(1, L + 1):
+            for t in range(s + 1, L + 1):
+                sweep = [(F_CK, s)] + [(F_NULL, j) for j in range(s + 1, t)]
+                _, peak = simulate(sweep, s, t, uf, ub, wa, wabar, wd, of, ob, complete=False)
+                if _m_null(wa, wd, of, s, t, mistake) != peak:
+                    return True
+    return False
+
+
+def test_unmodified_m_null_matches_the_simulated_sweep():
+    assert not _m_null_disagrees_with_simulated_sweep(None)
+
+
+@pytest.mark.parametrize("mistake", M_NULL_MISTAKES)
+def test_planted_m_null_mistake_is_caught(mistake):
+    assert _m_null_disagrees_with_simulated_sweep(mistake), mistake
+
+
 @pytest.mark.parametrize("cfg", [0, 1])
 def test_second_opinion_on_c_oracle(oracle_mod, cfg):
     batch = make_config(cfg)
@@ -128,7 +179,9 @@ def test_second_opinion_on_c_oracle(oracle_mod, cfg):
 
 
 def test_second_opinion_when_abar_smaller_than_a(oracle_mod):
-    """Inputs that break omega_abar >= omega_a: both evaluations follow the printed formulas."""
+    """Inputs that break omega_abar >= omega_a are outside the Theorem's model; the C oracle and
+    the Python evaluation still agree on what the printed formulas give (formula conformance,
+    not parity with an optimum)."""
     rng = np.random.default_rng(9)
     L, M = 9, 60
     uf = rng.integers(1, 50, L); ub = rng.integers(1, 90, L)
@@ -138,3 +191,20 @@ def test_second_opinion_when_abar_smaller_than_a(oracle_mod):
     C, K = py_table(L, M, *[a.tolist() for a in (uf, ub, wa, wabar, wd, of, ob)])
     for (s, t), row in C.items():
         assert cost[s - 1, t - 1].tolist() == row and choice[s - 1, t - 1].tolist() == K[s, t]
+
+
+def test_the_theorem_needs_abar_to_contain_a(oracle_mod):
+    """Why omega_abar >= omega_a is a precondition of the library: without it the recurrence is
+    not the optimum over persistent schedules any more (the brute force finds cheaper or
+    earlier-fitting schedules), so such inputs have no exact answer to be compared with."""
+    rng = np.random.default_rng(5)
+    differs = 0
+    for _ in range(25):
+        L, M = int(rng.integers(3, 6)), 40
+        uf = rng.integers(1, 50, L); ub = rng.integers(1, 90, L)
+        wa = rng.integers(1, 9, L + 1); wabar = rng.integers(0, 6, L)
+        wd = rng.integers(0, 7, L + 1); of = rng.integers(0, 4, L); ob = rng.integers(0, 4, L)
+        cost, _ = oracle_mod.solve_chain(L, M, uf, ub, wa, wabar, wd, of, ob)
+        best, _ = brute_force_segment(1, L, M, uf, ub, wa, wabar, wd, of, ob, INF)
+        differs += cost[0, L - 1].tolist() != best
+    assert differs > 0
