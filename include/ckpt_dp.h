@@ -36,11 +36,12 @@
  *
  * Ownership and threading: every buffer belongs to the caller and must stay valid
  * until the work enqueued on the stream has finished.  The library's only state is the
- * last HIP error code and, per device, three helper streams with four events that
- * ckpt_solve_batched creates on its first large solve there and keeps (it runs up to
- * three quarters of a batch on them, forked from and joined back into the caller's
- * stream).  Calls from several threads and on different streams with disjoint
- * buffers are safe; their enqueueing is serialised per device.
+ * last HIP error code and, per device, three helper streams with four events (see
+ * ckpt_init) on which ckpt_solve_batched runs up to three quarters of a large batch,
+ * forked from and joined back into the caller's stream.  A solve with
+ * ckpt_solve_opts_t.groups = 1 touches none of it.  Calls from several threads and on
+ * different streams with disjoint buffers are safe; the enqueueing of split solves is
+ * serialised per device.
  *
  * Errors: every function that can fail returns CKPT_OK (0) or a negative code and
  * never throws or aborts.  Argument errors are reported before anything is
@@ -67,7 +68,8 @@ enum {
     CKPT_E_SMALLBUF = -4,   /* ckpt_schedule: ops_cap too small (2L-1 .. L(L+1)/2+L operations) */
     CKPT_E_HIP = -5,        /* a HIP call failed; see ckpt_last_hip_error() */
     CKPT_E_INPUT = -6,      /* ckpt_check_inputs: some chain violates the value preconditions */
-    CKPT_E_CORRUPT = -7     /* ckpt_schedule: the arg table is not one this library wrote */
+    CKPT_E_CORRUPT = -7,    /* the arg table or operation list is not one this library wrote */
+    CKPT_E_NOTREADY = -8    /* helper streams are missing and cannot be created now (stream capture) */
 };
 
 /*
@@ -76,7 +78,9 @@ enum {
  * [b*(L+1) + i] of the [B][L+1] arrays.
  * Preconditions on values (checked on the device, see ckpt_check_inputs): all >= 0;
  * sum of u_f of a chain < 2^30 and every u_b < 2^30; every size and overhead
- * <= 2^28.  Costs that reach 2^30 saturate to CKPT_INF exactly as defined above.
+ * <= 2^28; omega_abar^k >= omega_a^k for every stage (abar^k contains a^k: without it
+ * the Theorem is not the optimum over persistent schedules).  Costs that reach 2^30
+ * saturate to CKPT_INF exactly as defined above.
  */
 typedef struct ckpt_chains {
     const int32_t* uf;     /* [B][L]   u_f^k + u_fcomm^k            (Tables 1, 2) */
@@ -107,13 +111,24 @@ size_t ckpt_table_elems(int L, int M, int B);
 size_t ckpt_workspace_bytes(int L, int M, int B);
 
 /*
+ * Set-up for one device (device < 0: the current one): creates the helper streams and events
+ * of the batch split and sets the kernel attributes a solve needs.  Idempotent and
+ * thread-safe; what it creates lives until the process ends.  ckpt_solve_batched does the
+ * same on its first large solve on a device, except when its stream is being captured into
+ * a HIP graph (nothing is created behind a capture: the solve then runs unsplit); call
+ * ckpt_init first to capture split solves.
+ * Returns CKPT_OK, CKPT_E_LIMIT (device >= 64) or CKPT_E_HIP.
+ */
+int ckpt_init(int device);
+
+/*
  * Fill cost and arg for all B chains (Theorem, all three displays: the recurrence,
  * C_ck / C_all, and the thresholds m_null / m_all).
  *   chains    host pointer to a struct of DEVICE pointers (read during the call
  *             only; the arrays it names are read by the enqueued kernels)
  *   stream    a hipStream_t (NULL = the default stream); the call only enqueues
- *             work and returns, it does not synchronise and allocates no memory
- *             (see the helper streams above); it may be captured into a HIP graph
+ *             work and returns, it does not synchronise and allocates no device
+ *             memory; it may be captured into a HIP graph
  *   cost, arg DEVICE tables laid out as above, 256-byte aligned
  *   workspace DEVICE memory of ckpt_workspace_bytes(L, M, B) bytes, 256-byte
  *             aligned; holds per-chain prefix sums, thresholds and input flags
@@ -121,6 +136,30 @@ size_t ckpt_workspace_bytes(int L, int M, int B);
  */
 int ckpt_solve_batched(const ckpt_chains_t* chains, int L, int M, int B, void* stream,
                        int32_t* cost, uint8_t* arg, void* workspace);
+
+/*
+ * The same fill with the schedule under the caller's control.  The tables do not depend on
+ * any of these choices, bit for bit.
+ *   groups        0: automatic (a large batch is cut into up to four groups of chains that run
+ *                 on four streams).  1: everything on `stream`; no helper stream, event or
+ *                 lock of the library is touched.  2..4: that many groups (at most B), also on
+ *                 small batches.
+ *   side_streams  caller-owned hipStream_t for groups 2, 3, 4, or all NULL: the library's
+ *                 helper streams.  The fork and join events are the library's in both cases.
+ *   list_split    0: automatic.  1, 2 or 4: waves that share one chunk's list of splits in
+ *                 every launch of the block-product kernel.
+ *   reserved      zeros
+ * opts == NULL is ckpt_solve_batched.  Returns as ckpt_solve_batched, plus CKPT_E_NOTREADY
+ * when groups > 1 is requested while `stream` is being captured and ckpt_init has not run.
+ */
+typedef struct ckpt_solve_opts {
+    int groups;
+    void* side_streams[3];
+    int list_split;
+    int reserved[3];
+} ckpt_solve_opts_t;
+int ckpt_solve_batched_opts(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
+                            uint8_t* arg, void* workspace, const ckpt_solve_opts_t* opts);
 
 /*
  * Measurement aid: the same fill as ckpt_solve_batched, with a HIP event recorded on
@@ -142,23 +181,42 @@ const char* ckpt_kernel_name(int kind);
  * per-chain input flags (0 = chain met the value preconditions) into flags_host[B]
  * (HOST memory).  Returns CKPT_OK, CKPT_E_INPUT if any flag is nonzero (the
  * tables of such a chain are unspecified, all memory accesses stayed in bounds),
- * CKPT_E_ARG or CKPT_E_HIP.  Bits: 1 negative value, 2 time too large, 4 size too large.
+ * CKPT_E_ARG or CKPT_E_HIP.  Bits: 1 negative value, 2 time too large, 4 size too large,
+ * 8 some omega_abar^k below its omega_a^k (the tables of such a chain follow the printed
+ * formulas, which are then no longer the optimum over persistent schedules).
  */
 int ckpt_check_inputs(const void* workspace, int L, int M, int B, void* stream, int32_t* flags_host);
 
 /*
  * Rebuild the operation sequence that realises C_BP(s, t, m_budget) of ONE chain
  * from its recorded candidates (C_ck / C_all of the Theorem read backwards; the
- * operations are those of Table 1, and consecutive F_null runs are what the
- * code generator of Section "Code generation" wraps in a checkpoint block).
+ * operations are those of Table 1).
  *   arg_host  HOST copy of that chain's arg table [rows][pitch]
  *   wa, wabar HOST arrays of that chain: omega_a^0..L [L+1], omega_abar^1..L [L]
+ *   m_budget  memory for the segment, its input not counted; values above M read column M
+ *             (as in ckpt_schedule_batched and ckpt_select_plan), negative values are an error
  *   ops_out   HOST array of ops_cap operations, written in execution order
  * Returns the number of operations (>= 2), or CKPT_E_ARG, CKPT_E_LIMIT,
  * CKPT_E_INFEASIBLE, CKPT_E_SMALLBUF, CKPT_E_CORRUPT.  Runs on the host only.
  */
 int ckpt_schedule(const uint8_t* arg_host, const int32_t* wa, const int32_t* wabar, int L, int M,
                   int s, int t, int m_budget, ckpt_op_t* ops_out, int ops_cap);
+
+/*
+ * Activation-checkpoint block index of every stage (Section "Code generation": every node is
+ * annotated with the index of its checkpoint block, and the nodes of one index are packaged
+ * into one function that is wrapped in the framework's checkpoint call, which keeps the
+ * block's input and recomputes its inside during the backward phase).  Read off an
+ * operation list of the WHOLE chain (s = 1, t = L) as ckpt_schedule writes it: a stage's
+ * annotation comes from its first forward operation -- F_ck^j opens a new block (only its
+ * input is kept), F_null^j continues the block of stage j-1, F_all^j keeps abar^j and lies in
+ * no block.  Later forwards of a stage are the recomputation and change nothing.
+ *   ops, n_ops       HOST operation list
+ *   block_of_stage   HOST out [L]: block number 0, 1, ... in chain order, -1 = in no block
+ * Returns the number of blocks, or CKPT_E_ARG, CKPT_E_LIMIT, CKPT_E_CORRUPT (not the list of
+ * a whole chain).  Runs on the host only.
+ */
+int ckpt_block_indices(const ckpt_op_t* ops, int n_ops, int L, int32_t* block_of_stage);
 
 /*
  * Planner-side steps around the table fill (Section "Integrate Two Solvers": the planner
@@ -234,6 +292,19 @@ int ckpt_schedule_batched(const uint8_t* arg, const int32_t* wa, const int32_t* 
                           void* workspace);
 /* Bytes of DEVICE workspace (16-byte aligned) ckpt_schedule_batched needs: the walk stacks. */
 size_t ckpt_schedule_workspace_bytes(int L, int B);
+
+/*
+ * ckpt_block_indices for every chain at once, on the device, from the output of
+ * ckpt_schedule_batched.
+ *   ops, ops_cap, n_ops   DEVICE, as written by ckpt_schedule_batched
+ *   block_of_stage        DEVICE int32 [B][L]; all -1 for a chain without a valid list
+ *   n_blocks              DEVICE int32 [B]: number of blocks of chain b; n_ops[b] itself if that
+ *                         is negative; CKPT_E_ARG if n_ops[b] > ops_cap; CKPT_E_CORRUPT if the
+ *                         list is not that of a whole chain
+ * Returns CKPT_OK, CKPT_E_ARG, CKPT_E_LIMIT or CKPT_E_HIP.
+ */
+int ckpt_block_indices_batched(const ckpt_op_t* ops, int ops_cap, const int32_t* n_ops, int L, int B, void* stream,
+                               int32_t* block_of_stage, int32_t* n_blocks);
 
 /*
  * Self-check of operation lists on the device: the list of every chain is executed over

@@ -34,6 +34,11 @@ class _Op(ctypes.Structure):
     _fields_ = [("kind", ctypes.c_uint8), ("stage", ctypes.c_uint8)]
 
 
+class _SolveOpts(ctypes.Structure):
+    _fields_ = [("groups", ctypes.c_int), ("side_streams", ctypes.c_void_p * 3), ("list_split", ctypes.c_int),
+                ("reserved", ctypes.c_int * 3)]
+
+
 def lib_path() -> str:
     return _LIB_PATH
 
@@ -58,6 +63,14 @@ def load_library():
     lib.ckpt_workspace_bytes.restype, lib.ckpt_workspace_bytes.argtypes = sz, [i, i, i]
     lib.ckpt_solve_batched.restype = i
     lib.ckpt_solve_batched.argtypes = [ctypes.POINTER(_Chains), i, i, i, vp, vp, vp, vp]
+    lib.ckpt_init.restype, lib.ckpt_init.argtypes = i, [i]
+    lib.ckpt_solve_batched_opts.restype = i
+    lib.ckpt_solve_batched_opts.argtypes = [ctypes.POINTER(_Chains), i, i, i, vp, vp, vp, vp,
+                                            ctypes.POINTER(_SolveOpts)]
+    lib.ckpt_block_indices.restype = i
+    lib.ckpt_block_indices.argtypes = [ctypes.POINTER(_Op), i, i, vp]
+    lib.ckpt_block_indices_batched.restype = i
+    lib.ckpt_block_indices_batched.argtypes = [vp, i, vp, i, i, vp, vp, vp]
     lib.ckpt_solve_profiled.restype = i
     lib.ckpt_solve_profiled.argtypes = [ctypes.POINTER(_Chains), i, i, i, vp, vp, vp, vp, vp, vp]
     lib.ckpt_kernel_name.restype, lib.ckpt_kernel_name.argtypes = ctypes.c_char_p, [i]
@@ -164,6 +177,28 @@ def ckpt_solve_batched(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, *, wdel
         raise CkptError(rc, "ckpt_solve_batched")
 
 
+def ckpt_init(device: int = -1) -> None:
+    """Create the library's per-device helper streams and events (device < 0: the current one)."""
+    rc = load_library().ckpt_init(device)
+    if rc != 0:
+        raise CkptError(rc, "ckpt_init")
+
+
+def ckpt_solve_batched_opts(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, *, groups=0, side_streams=None,
+                            list_split=0, wdelta=None, of=None, ob=None, stream=None) -> None:
+    """ckpt_solve_batched with the schedule chosen by the caller: number of chain groups (1 = no
+    helper streams), caller-owned side streams (raw hipStream_t values), waves per work list."""
+    ch, st = _marshal(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, wdelta, of, ob, stream)
+    opts = _SolveOpts()
+    opts.groups, opts.list_split = groups, list_split
+    for k, h in enumerate(side_streams or []):
+        opts.side_streams[k] = h
+    rc = load_library().ckpt_solve_batched_opts(ctypes.byref(ch), L, M, B, st, cost.data_ptr(), arg.data_ptr(),
+                                                workspace.data_ptr(), ctypes.byref(opts))
+    if rc != 0:
+        raise CkptError(rc, "ckpt_solve_batched_opts")
+
+
 def ckpt_check_inputs(workspace, L, M, B, *, stream=None) -> np.ndarray:
     """Synchronise and return the per-chain input flags (all zero = fine); raises on nonzero."""
     import torch
@@ -191,6 +226,19 @@ def ckpt_schedule(arg_host: np.ndarray, wa: np.ndarray, wabar: np.ndarray, L: in
     if rc < 0:
         raise CkptError(rc, "ckpt_schedule")
     return [(ops[i].kind, ops[i].stage) for i in range(rc)]
+
+
+def ckpt_block_indices(ops, L):
+    """Host: checkpoint block index of every stage from a whole-chain operation list
+    [(kind, stage), ...]; returns (list of L indices, number of blocks)."""
+    arr = (_Op * max(len(ops), 1))()
+    for k, (kind, stage) in enumerate(ops):
+        arr[k].kind, arr[k].stage = kind, stage
+    out = np.empty(max(L, 1), np.int32)
+    rc = load_library().ckpt_block_indices(arr, len(ops), L, out.ctypes.data)
+    if rc < 0:
+        raise CkptError(rc, "ckpt_block_indices")
+    return out[:L].tolist(), rc
 
 
 def _stream(stream):
@@ -278,6 +326,17 @@ def ckpt_schedule_batched(arg, wa, wabar, L, M, B, m_budget, ops, ops_cap, n_ops
         raise CkptError(rc, "ckpt_schedule_batched")
 
 
+def ckpt_block_indices_batched(ops, ops_cap, n_ops, L, B, block_of_stage, n_blocks, *, stream=None) -> None:
+    """Device: block_of_stage int32 [B, L], n_blocks int32 [B] from the lists of ckpt_schedule_batched."""
+    import torch
+    rc = load_library().ckpt_block_indices_batched(
+        _dev(ops, "ops", torch.uint8, B * ops_cap * 2), ops_cap, _dev(n_ops, "n_ops", torch.int32, B), L, B,
+        _stream(stream), _dev(block_of_stage, "block_of_stage", torch.int32, B * L),
+        _dev(n_blocks, "n_blocks", torch.int32, B))
+    if rc != 0:
+        raise CkptError(rc, "ckpt_block_indices_batched")
+
+
 def ckpt_simulate_batched(uf, ub, wa, wabar, L, B, ops, ops_cap, n_ops, time_out, peak_out, status, *, wdelta=None,
                           of=None, ob=None, stream=None) -> None:
     """Device execution of every chain's operation list under the memory model of Table 1:
@@ -323,8 +382,9 @@ class Solution:
     workspace: "object"
 
 
-def solve(batch, device="cuda:0", check=True) -> Solution:
-    """Convenience wrapper: upload a workloads.ChainBatch-like object, allocate tables, solve."""
+def solve(batch, device="cuda:0", check=True, **opts) -> Solution:
+    """Convenience wrapper: upload a workloads.ChainBatch-like object, allocate tables, solve.
+    Keyword options (groups, side_streams, list_split) go to ckpt_solve_batched_opts."""
     import torch
     dev = torch.device(device)
     L, M, B = batch.L, batch.M, batch.B
@@ -337,8 +397,9 @@ def solve(batch, device="cuda:0", check=True) -> Solution:
         cost = torch.empty((B, rows, pitch), dtype=torch.int32, device=dev)
         arg = torch.empty((B, rows, pitch), dtype=torch.uint8, device=dev)
         ws = torch.empty(ckpt_workspace_bytes(L, M, B), dtype=torch.uint8, device=dev)
-        ckpt_solve_batched(up(batch.uf), up(batch.ub), up(batch.wa), up(batch.wabar), L, M, B, cost, arg, ws,
-                           wdelta=up(batch.wdelta), of=up(batch.of), ob=up(batch.ob))
+        fill = ckpt_solve_batched_opts if opts else ckpt_solve_batched
+        fill(up(batch.uf), up(batch.ub), up(batch.wa), up(batch.wabar), L, M, B, cost, arg, ws,
+             wdelta=up(batch.wdelta), of=up(batch.of), ob=up(batch.ob), **opts)
         if check:
             flags = ckpt_check_inputs(ws, L, M, B)
             if flags.any():

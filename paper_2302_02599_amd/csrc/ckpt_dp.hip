@@ -152,6 +152,7 @@ __global__ void __launch_bounds__(256) precompute_kernel(ckpt_chains_t ch, int L
             if (v < 0) flags |= 1;
             if (v > (1 << 28)) flags |= 4;
         }
+        if (wab[k] < wa[k + 1]) flags |= 8;  // abar^k must contain a^k: outside the Theorem's model
         if (k == 0) {
             if (wa[0] < 0 || wd[0] < 0) flags |= 1;
             if (wa[0] > (1 << 28) || wd[0] > (1 << 28)) flags |= 4;
@@ -791,6 +792,54 @@ __global__ void __launch_bounds__(64) schedule_kernel(const uint8_t* __restrict_
     n_ops[b] = err ? err : n;
 }
 
+// Checkpoint block index of every stage (Section "Code generation"): one wave per chain reads the
+// first forward sweep of its operation list.  In a list produced by the walk above, operation k
+// (k < L) is the first forward of stage k + 1 and operation L is B^L; F_ck opens a block, F_null
+// continues it, F_all lies in none.  The block number of a stage is the count of F_ck up to it,
+// minus one: an inclusive prefix sum over the lanes, carried across passes of 64 stages.
+__global__ void __launch_bounds__(64) block_index_kernel(const ckpt_op_t* __restrict__ ops, int cap,
+                                                          const int32_t* __restrict__ n_ops, int L,
+                                                          int32_t* __restrict__ block_of_stage,
+                                                          int32_t* __restrict__ n_blocks) {
+    const int b = blockIdx.x, lane = threadIdx.x;
+    const int n = n_ops[b];
+    int32_t* out = block_of_stage + size_t(b) * L;
+    if (n < 0 || n > cap || n < L + 1) {  // uniform: a failed walk keeps its code, a short list is corrupt
+        for (int k = lane; k < L; k += 64) out[k] = -1;
+        if (lane == 0) n_blocks[b] = n < 0 ? n : (n > cap ? CKPT_E_ARG : CKPT_E_CORRUPT);
+        return;
+    }
+    const ckpt_op_t* list = ops + size_t(b) * cap;
+    int carry = 0;       // F_ck seen in earlier passes
+    int prev_in = 0;     // was the last stage of the previous pass inside a block
+    bool bad = false;
+    for (int base = 0; base < L; base += 64) {  // L is uniform: every lane takes every pass
+        const int k = base + lane;
+        const bool valid = k < L;
+        const int kind = valid ? list[k].kind : CKPT_OP_F_ALL;
+        const int stage = valid ? list[k].stage : k + 1;
+        const bool opens = valid && kind == CKPT_OP_F_CK;
+        const bool inside = valid && (kind == CKPT_OP_F_CK || kind == CKPT_OP_F_NULL);
+        int before = __shfl_up(int(inside), 1);
+        if (lane == 0) before = prev_in;
+        if (valid && (stage != k + 1 || kind > CKPT_OP_F_NULL || (kind == CKPT_OP_F_NULL && !before))) bad = true;
+        int scan = int(opens);
+#pragma unroll
+        for (int o = 1; o < 64; o <<= 1) {
+            const int v = __shfl_up(scan, o);
+            if (lane >= o) scan += v;
+        }
+        if (valid) out[k] = inside ? carry + scan - 1 : -1;
+        carry += __shfl(scan, 63);
+        prev_in = __shfl(int(inside), 63);
+    }
+    if (lane == 0 && (list[L].kind != CKPT_OP_B || list[L].stage != L)) bad = true;
+    bad = __any(bad);
+    if (bad)
+        for (int k = lane; k < L; k += 64) out[k] = -1;
+    if (lane == 0) n_blocks[b] = bad ? CKPT_E_CORRUPT : carry;
+}
+
 // Self-check of operation lists: one wave per chain executes its list under the memory model
 // of Table 1 ("List of Operations").  The lanes stage the chain's arrays and the list through
 // LDS; lane 0 carries the state: per stage j one byte with bit 0 = a^j resident on its own,
@@ -902,58 +951,86 @@ struct Profile {
         if (prof && !prof->mark(kind)) return CKPT_E_HIP;         \
     } while (0)
 
-// Streams of the batch split beside the caller's, per device, created on first use and kept
-// for the life of the process (default priority, non-blocking).  With the caller's stream they
-// make four, the number of hardware queues a process gets by default; more streams than that
-// share queues and serialise (measured: six or eight groups are slower than one).
+// Per-device state of the library, kept for the life of the process:
+//   helpers  three streams (default priority, non-blocking) and four events for the batch split;
+//            with the caller's stream they make four, the number of hardware queues a process
+//            gets by default (more streams than that share queues and serialise: six or eight
+//            groups measured slower than one).  Created by ckpt_init or by the first solve
+//            that wants to split, never while that solve's stream is being captured.
 constexpr int kSideStreams = 3;
-struct Side {
+struct Device {
     hipStream_t stream[kSideStreams] = {};
     hipEvent_t join[kSideStreams] = {};
     hipEvent_t fork = nullptr;
-    bool tried = false, ok = false;
-    std::mutex busy;
+    bool helpers_tried = false, helpers_ok = false;
+    std::mutex busy;  // one fork/join sequence at a time per device
 };
 
-Side* side_streams() {
-    static Side table[64];
-    static std::mutex init;
+std::mutex g_devices_lock;
+Device g_devices[64];
+
+Device* current_device() {
     int dev = 0;
     if (!hip_ok(hipGetDevice(&dev)) || dev < 0 || dev >= 64) return nullptr;
-    Side& s = table[dev];
-    std::lock_guard<std::mutex> guard(init);
-    if (!s.tried) {
-        s.tried = true;
-        s.ok = hip_ok(hipEventCreateWithFlags(&s.fork, hipEventDisableTiming));
-        for (int k = 0; k < kSideStreams && s.ok; ++k)
-            s.ok = hip_ok(hipStreamCreateWithFlags(&s.stream[k], hipStreamNonBlocking)) &&
-                   hip_ok(hipEventCreateWithFlags(&s.join[k], hipEventDisableTiming));
+    return &g_devices[dev];
+}
+
+// Both set-up steps run with the device current and under g_devices_lock.
+bool ensure_helpers(Device& d) {
+    std::lock_guard<std::mutex> guard(g_devices_lock);
+    if (!d.helpers_tried) {
+        d.helpers_tried = true;
+        bool ok = hip_ok(hipEventCreateWithFlags(&d.fork, hipEventDisableTiming));
+        for (int k = 0; k < kSideStreams && ok; ++k)
+            ok = hip_ok(hipStreamCreateWithFlags(&d.stream[k], hipStreamNonBlocking)) &&
+                 hip_ok(hipEventCreateWithFlags(&d.join[k], hipEventDisableTiming));
+        d.helpers_ok = ok;
     }
-    return s.ok ? &s : nullptr;
+    return d.helpers_ok;
+}
+
+bool helpers_ready(Device& d) {
+    std::lock_guard<std::mutex> guard(g_devices_lock);
+    return d.helpers_ok;
+}
+
+// The frontier kernel keeps its triangle in LDS; above the default per-block limit it has to be
+// allowed the size.  Set once (to the largest size any L can need); allocates nothing.
+bool allow_frontier_lds() {
+    static std::once_flag once;
+    static bool ok = false;
+    std::call_once(once, [] {
+        ok = hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(frontier_kernel),
+                                        hipFuncAttributeMaxDynamicSharedMemorySize,
+                                        int(ckpt_table_rows(CKPT_MAX_L) * sizeof(int32_t))));
+    });
+    return ok;
 }
 
 int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost, uint8_t* arg,
-               void* workspace, Profile* prof) {
+               void* workspace, Profile* prof, const ckpt_solve_opts_t* opts, bool may_create_helpers) {
     if (!chains || !cost || !arg || !workspace) return CKPT_E_ARG;
     if (int rc = check_dims(L, M, B)) return rc;
     if (!chains->uf || !chains->ub || !chains->wa || !chains->wabar) return CKPT_E_ARG;
     if ((reinterpret_cast<uintptr_t>(cost) | reinterpret_cast<uintptr_t>(arg) |
          reinterpret_cast<uintptr_t>(workspace)) & 255)
         return CKPT_E_ARG;
+    const int want_groups = opts ? opts->groups : 0, want_ks = opts ? opts->list_split : 0;
+    if (want_groups < 0 || want_groups > kSideStreams + 1) return CKPT_E_ARG;
+    if (want_ks != 0 && want_ks != 1 && want_ks != 2 && want_ks != 4) return CKPT_E_ARG;
+    bool own_side = false;
+    if (opts) {
+        for (int k = 0; k < kSideStreams; ++k) own_side = own_side || opts->side_streams[k];
+        for (int k = 0; k < kSideStreams && own_side; ++k)
+            if (!opts->side_streams[k] && k + 2 <= (want_groups ? want_groups : kSideStreams + 1)) return CKPT_E_ARG;
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int pitch = int(ckpt_row_pitch(M));
     const int rows = int(ckpt_table_rows(L));
     const Workspace ws = carve(workspace, L, B);
 
     const size_t frontier_lds = ckpt_table_rows(L) * sizeof(int32_t);
-    if (frontier_lds > 48 * 1024) {
-        // Above the default per-block limit the kernel has to be allowed its LDS size; this sets a
-        // function attribute (to the largest size any L can need) and allocates nothing.
-        if (!hip_ok(hipFuncSetAttribute(reinterpret_cast<const void*>(frontier_kernel),
-                                        hipFuncAttributeMaxDynamicSharedMemorySize,
-                                        int(ckpt_table_rows(CKPT_MAX_L) * sizeof(int32_t)))))
-            return CKPT_E_HIP;
-    }
+    if (frontier_lds > 48 * 1024 && !allow_frontier_lds()) return CKPT_E_HIP;
     constexpr int T = kT;
     const int nblk = (L + T - 1) / T;
     const int gx_row = (pitch + kRowWG - 1) / kRowWG;
@@ -965,19 +1042,42 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     // the first side stream next to the D = 0 and D = 1 rows of the whole batch, which do not
     // need it.  The side streams are forked from and joined back into the caller's stream with
     // events.  Small problems are bound by launch latency, where more streams only add launches.
-    const bool split = !prof && B >= 2 && nblk >= 3 && size_t(B) * nblk * pitch >= (size_t(1) << 19);
-    Side* side = split ? side_streams() : nullptr;
+    // Automatic choice: split when the batch is large enough to be bound by the GPU and not by
+    // launch latency (where more streams only add launches).  The caller can force either way.
+    const bool large = B >= 2 && size_t(B) * nblk * pitch >= (size_t(1) << 19);
+    int groups = want_groups ? want_groups : (large ? kSideStreams + 1 : 1);
+    groups = std::min(groups, B);
+    if (prof || nblk < 3) groups = 1;  // the event trail times one stream; no diagonal to split
+    Device* dev = nullptr;
+    if (groups > 1) {
+        dev = current_device();
+        if (!dev) return CKPT_E_HIP;
+        if (!helpers_ready(*dev)) {
+            // Streams and events are not created behind a capture: a captured stream must only see
+            // enqueued work.  ckpt_init beforehand makes the split available to captured solves.
+            hipStreamCaptureStatus cap = hipStreamCaptureStatusNone;
+            if (!hip_ok(hipStreamIsCapturing(st, &cap))) return CKPT_E_HIP;
+            if (cap != hipStreamCaptureStatusNone || !may_create_helpers) {
+                if (want_groups > 1) return CKPT_E_NOTREADY;
+                groups = 1;
+            } else if (!ensure_helpers(*dev)) {
+                return CKPT_E_HIP;
+            }
+        }
+    }
+    Device* side = groups > 1 ? dev : nullptr;
     std::unique_lock<std::mutex> lock;
     if (side) lock = std::unique_lock<std::mutex>(side->busy);  // one fork/join at a time per device
-    const int groups = side ? std::min(B, kSideStreams + 1) : 1;
     hipStream_t gs[kSideStreams + 1] = {st, st, st, st};  // stream of group g
-    for (int g = 1; g < groups; ++g) gs[g] = side->stream[g - 1];
+    hipStream_t side_stream[kSideStreams] = {};
+    for (int g = 1; g < groups; ++g)
+        gs[g] = side_stream[g - 1] = own_side ? static_cast<hipStream_t>(opts->side_streams[g - 1]) : side->stream[g - 1];
     int first[kSideStreams + 2];  // group g holds chains first[g] .. first[g + 1] - 1
     for (int g = 0; g <= groups; ++g) first[g] = int((long long)B * g / groups);
 
     int forked = 0;  // side streams that wait on the caller's stream and have to be joined back
     auto join_side = [&](int k) {  // the caller's stream waits for side stream k
-        return hip_ok(hipEventRecord(side->join[k], side->stream[k])) &&
+        return hip_ok(hipEventRecord(side->join[k], side_stream[k])) &&
                hip_ok(hipStreamWaitEvent(st, side->join[k], 0));
     };
     auto enqueue = [&]() -> int {
@@ -1011,7 +1111,7 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
             // The last diagonals have few tiles: when all groups together bring fewer waves than
             // the chip holds, 2 or 4 waves share each chunk and split its work list.
             const long long waves = (long long)(nblk - D) * (pitch / 64) * B;
-            const int ks = waves <= 600 ? 4 : (waves <= 1700 ? 2 : 1);
+            const int ks = want_ks ? want_ks : (waves <= 600 ? 4 : (waves <= 1700 ? 2 : 1));
             const int gx = (pitch / 64 + kCH / ks - 1) / (kCH / ks);
             for (int g = 0; g < groups; ++g) {
                 const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
@@ -1068,9 +1168,27 @@ size_t ckpt_workspace_bytes(int L, int M, int B) {
     return ws_ints(L, B) * sizeof(int32_t);
 }
 
+int ckpt_init(int device) {
+    if (device >= 64) return CKPT_E_LIMIT;
+    int prev = 0;
+    if (!hip_ok(hipGetDevice(&prev))) return CKPT_E_HIP;
+    if (device < 0) device = prev;
+    if (device >= 64) return CKPT_E_LIMIT;
+    if (device != prev && !hip_ok(hipSetDevice(device))) return CKPT_E_HIP;
+    Device& d = g_devices[device];
+    const bool ok = ensure_helpers(d) && allow_frontier_lds();
+    if (device != prev && !hip_ok(hipSetDevice(prev))) return CKPT_E_HIP;
+    return ok ? CKPT_OK : CKPT_E_HIP;
+}
+
 int ckpt_solve_batched(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
                        uint8_t* arg, void* workspace) {
-    return solve_impl(chains, L, M, B, stream, cost, arg, workspace, nullptr);
+    return solve_impl(chains, L, M, B, stream, cost, arg, workspace, nullptr, nullptr, true);
+}
+
+int ckpt_solve_batched_opts(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
+                            uint8_t* arg, void* workspace, const ckpt_solve_opts_t* opts) {
+    return solve_impl(chains, L, M, B, stream, cost, arg, workspace, nullptr, opts, true);
 }
 
 int ckpt_solve_profiled(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
@@ -1082,7 +1200,7 @@ int ckpt_solve_profiled(const ckpt_chains_t* chains, int L, int M, int B, void* 
     for (int k = 0; k < CKPT_N_KERNEL_KINDS; ++k) kind_ms[k] = 0.f, kind_launches[k] = 0;
     int rc = CKPT_OK;
     if (!prof.mark(-1)) rc = CKPT_E_HIP;
-    if (rc == CKPT_OK) rc = solve_impl(chains, L, M, B, stream, cost, arg, workspace, &prof);
+    if (rc == CKPT_OK) rc = solve_impl(chains, L, M, B, stream, cost, arg, workspace, &prof, nullptr, false);
     if (!hip_ok(hipStreamSynchronize(st)) && rc == CKPT_OK) rc = CKPT_E_HIP;
     for (size_t i = 1; i < prof.events.size() && rc == CKPT_OK; ++i) {
         float ms = 0.f;
@@ -1213,6 +1331,15 @@ int ckpt_schedule_batched(const uint8_t* arg, const int32_t* wa, const int32_t* 
     return hip_ok(hipGetLastError()) ? CKPT_OK : CKPT_E_HIP;
 }
 
+int ckpt_block_indices_batched(const ckpt_op_t* ops, int ops_cap, const int32_t* n_ops, int L, int B, void* stream,
+                               int32_t* block_of_stage, int32_t* n_blocks) {
+    if (!ops || !n_ops || !block_of_stage || !n_blocks || ops_cap < 0 || L < 1 || B < 1) return CKPT_E_ARG;
+    if (L > CKPT_MAX_L) return CKPT_E_LIMIT;
+    hipLaunchKernelGGL(block_index_kernel, dim3(B), dim3(64), 0, static_cast<hipStream_t>(stream), ops, ops_cap, n_ops,
+                       L, block_of_stage, n_blocks);
+    return hip_ok(hipGetLastError()) ? CKPT_OK : CKPT_E_HIP;
+}
+
 int ckpt_simulate_batched(const ckpt_chains_t* chains, int L, int B, const ckpt_op_t* ops, int ops_cap,
                           const int32_t* n_ops, void* stream, int64_t* time_out, int64_t* peak_out,
                           int32_t* status) {
@@ -1238,7 +1365,8 @@ const char* ckpt_strerror(int code) {
         case CKPT_E_SMALLBUF: return "output buffer too small";
         case CKPT_E_HIP: return "HIP call failed";
         case CKPT_E_INPUT: return "chain values violate the preconditions";
-        case CKPT_E_CORRUPT: return "arg table is inconsistent";
+        case CKPT_E_CORRUPT: return "arg table or operation list is inconsistent";
+        case CKPT_E_NOTREADY: return "helper streams do not exist yet and cannot be created now: call ckpt_init first";
         default: return "unknown error";
     }
 }

@@ -64,9 +64,34 @@ struct Walker {
 extern "C" int ckpt_schedule(const uint8_t* arg_host, const int32_t* wa, const int32_t* wabar, int L, int M,
                              int s, int t, int m_budget, ckpt_op_t* ops_out, int ops_cap) {
     if (!arg_host || !wa || !wabar || !ops_out || ops_cap < 0) return CKPT_E_ARG;
-    if (L < 1 || M < 0 || s < 1 || t < s || t > L || m_budget < 0 || m_budget > M) return CKPT_E_ARG;
+    if (L < 1 || M < 0 || s < 1 || t < s || t > L || m_budget < 0) return CKPT_E_ARG;
     if (L > CKPT_MAX_L) return CKPT_E_LIMIT;
     Walker w{arg_host, wa, wabar, L, M, ckpt_row_pitch(M), ops_out, ops_cap};
-    if (!w.walk(s, t, m_budget, true)) return w.err;
+    if (!w.walk(s, t, m_budget > M ? M : m_budget, true)) return w.err;  // the table ends at M
     return w.n;
+}
+
+// Checkpoint block index of every stage from an operation list over stages 1..L (Section "Code
+// generation").  The annotation of a stage comes from its first forward operation; the
+// operations before the first B are exactly the first forwards of stages 1..L, in order.
+extern "C" int ckpt_block_indices(const ckpt_op_t* ops, int n_ops, int L, int32_t* block_of_stage) {
+    if (!ops || !block_of_stage || L < 1 || n_ops < 0) return CKPT_E_ARG;
+    if (L > CKPT_MAX_L) return CKPT_E_LIMIT;
+    if (n_ops < L + 1) return CKPT_E_CORRUPT;
+    int blocks = 0;
+    for (int k = 0; k < L; ++k) {
+        const int kind = ops[k].kind;
+        if (ops[k].stage != k + 1) return CKPT_E_CORRUPT;
+        if (kind == CKPT_OP_F_ALL) {
+            block_of_stage[k] = -1;
+        } else if (kind == CKPT_OP_F_CK) {
+            block_of_stage[k] = blocks++;
+        } else if (kind == CKPT_OP_F_NULL && k > 0 && block_of_stage[k - 1] >= 0) {
+            block_of_stage[k] = block_of_stage[k - 1];
+        } else {
+            return CKPT_E_CORRUPT;
+        }
+    }
+    if (ops[L].kind != CKPT_OP_B || ops[L].stage != L) return CKPT_E_CORRUPT;
+    return blocks;
 }

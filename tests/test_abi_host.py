@@ -107,7 +107,10 @@ def test_schedule_error_codes(amd, oracle_mod):
     _, choice = oracle_mod.solve_chain(L, M, *ch)
     tab = _arg_table_from_oracle(amd, choice, L, M)
     full = amd.ckpt_schedule(tab, ch[2], ch[3], L, M, 1, L, M)
-    for bad in [dict(s=0), dict(t=L + 1), dict(s=3, t=2), dict(m_budget=-1), dict(m_budget=M + 1)]:
+    # a budget above the table's M reads column M, as in the batched walk and the plan selection
+    assert amd.ckpt_schedule(tab, ch[2], ch[3], L, M, 1, L, M + 1) == full
+    assert amd.ckpt_schedule(tab, ch[2], ch[3], L, M, 1, L, 2 ** 31 - 1) == full
+    for bad in [dict(s=0), dict(t=L + 1), dict(s=3, t=2), dict(m_budget=-1)]:
         kw = dict(s=1, t=L, m_budget=M); kw.update(bad)
         with pytest.raises(amd.CkptError) as e:
             amd.ckpt_schedule(tab, ch[2], ch[3], L, M, kw["s"], kw["t"], kw["m_budget"])
@@ -121,6 +124,67 @@ def test_schedule_error_codes(amd, oracle_mod):
     with pytest.raises(amd.CkptError) as e:
         amd.ckpt_schedule(broken, ch[2], ch[3], L, M, 1, L, M)
     assert e.value.code == -7
+
+
+def test_block_indices_host_matches_oracle(amd, oracle_mod):
+    """Section "Code generation": block index per stage from the whole-chain operation list; every
+    budget of cfg 0 and cfg 1, and every persistent schedule of short chains."""
+    from persistent_bruteforce import flatten, trees
+    for cfg in (0, 1):
+        batch = make_config(cfg)
+        L, M = batch.L, batch.M
+        ch = batch.chain(0)
+        cost, choice = oracle_mod.solve_chain(L, M, *ch)
+        tab = _arg_table_from_oracle(amd, choice, L, M)
+        kinds = set()
+        for m in range(M + 1):
+            if cost[0, L - 1, m] >= oracle_mod.INF:
+                continue
+            ops = amd.ckpt_schedule(tab, ch[2], ch[3], L, M, 1, L, m)
+            got = amd.ckpt_block_indices(ops, L)
+            assert got == oracle_mod.block_indices(ops, L), m
+            kinds.add(tuple(got[0]))
+        assert len(kinds) > 3
+    for L in (1, 2, 3, 4, 5):
+        for tree in trees(1, L):
+            ops = flatten(tree)
+            assert amd.ckpt_block_indices(ops, L) == oracle_mod.block_indices(ops, L)
+
+
+def test_block_indices_error_codes(amd):
+    A, C, N, B = 0, 1, 2, 3
+    ok = [(C, 1), (N, 2), (A, 3), (B, 3), (A, 1), (A, 2), (B, 2), (B, 1)]
+    assert amd.ckpt_block_indices(ok, 3) == ([0, 0, -1], 1)
+    for bad in ([(A, 1), (B, 1)],                            # shorter than the chain
+                [(A, 1), (N, 2), (A, 3), (B, 3)],            # F_null after a kept stage
+                [(N, 1), (A, 2), (B, 2)],                    # F_null^1 has nothing to continue
+                [(A, 2), (A, 1), (B, 2)],                    # stages out of order
+                [(A, 1), (A, 2), (A, 2)],                    # no B^L after the forward sweep
+                [(A, 1), (B, 2), (B, 2)]):
+        with pytest.raises(amd.CkptError) as e:
+            amd.ckpt_block_indices(bad, 2 if len(bad) == 3 else 3 if len(bad) > 3 else 2)
+        assert e.value.code == -7, bad
+    lib = amd.load_library()
+    assert lib.ckpt_block_indices(None, 3, 3, None) == -1
+    assert lib.ckpt_block_indices_batched(None, 4, 256, 3, 1, None, 256, 256) == -1
+    assert lib.ckpt_block_indices_batched(256, 4, 256, 255, 1, None, 256, 256) == -2
+
+
+def test_options_are_validated_on_the_host(amd):
+    lib = amd.load_library()
+    from paper_2302_02599_amd.binding import _Chains, _SolveOpts
+    ch = _Chains(256, 256, 256, 256, None, None, None)
+    f = lib.ckpt_solve_batched_opts
+    for groups, split in ((-1, 0), (5, 0), (0, 3), (0, 8), (0, -1)):
+        o = _SolveOpts()
+        o.groups, o.list_split = groups, split
+        assert f(ctypes.byref(ch), 4, 8, 1, None, 256, 256, 256, ctypes.byref(o)) == -1, (groups, split)
+    o = _SolveOpts()
+    o.groups = 3
+    o.side_streams[1] = 4096                                  # second side stream given, first missing
+    assert f(ctypes.byref(ch), 4, 8, 1, None, 256, 256, 256, ctypes.byref(o)) == -1
+    assert lib.ckpt_init(64) == -2
+    assert lib.ckpt_strerror(-8).startswith(b"helper streams")
 
 
 def test_schedule_worst_case_length_fits_default_capacity(amd):

@@ -97,7 +97,9 @@ def test_costs_saturate_at_the_sentinel(amd, oracle_mod):
     assert root == amd.CKPT_INF and one == 450_000_000
 
 
-def test_abar_smaller_than_a_follows_the_printed_formulas(amd, oracle_mod):
+def test_abar_smaller_than_a_is_flagged_and_follows_the_printed_formulas(amd, oracle_mod):
+    """Outside the Theorem's model (abar contains a): the chains are flagged (bit 8); their tables
+    are still what the printed formulas give -- formula conformance, not parity with an optimum."""
     rng = np.random.default_rng(23)
     L, M, B = 14, 90, 2
     batch = ChainBatch("abar_lt_a", L, M, B,
@@ -105,13 +107,17 @@ def test_abar_smaller_than_a_follows_the_printed_formulas(amd, oracle_mod):
                        wa=rng.integers(1, 9, (B, L + 1)).astype(np.int32), wabar=rng.integers(0, 6, (B, L)).astype(np.int32),
                        wdelta=rng.integers(0, 7, (B, L + 1)).astype(np.int32),
                        of=rng.integers(0, 4, (B, L)).astype(np.int32), ob=rng.integers(0, 4, (B, L)).astype(np.int32))
-    assert_tables_equal(oracle_mod, batch, amd.solve(batch))
+    batch.wabar[1] = np.maximum(batch.wabar[1], batch.wa[1, 1:])     # chain 1 is inside the model
+    sol = amd.solve(batch, check=False)
+    assert amd.ckpt_check_inputs(sol.workspace, L, M, B).tolist() == [8, 0]
+    assert_tables_equal(oracle_mod, batch, sol)
 
 
 def test_sizes_larger_than_the_budget(amd, oracle_mod):
     """A stage whose activation exceeds M + 1: shifts beyond the row stay in bounds and read as infeasible."""
     batch = random_chain_batch(10, 50, 2, 24, size_hi=6)
     batch.wa[:, 4] = 5000
+    batch.wabar[:, 3] = 5003
     batch.wabar[:, 6] = 70
     assert_tables_equal(oracle_mod, batch, amd.solve(batch))
 
@@ -135,6 +141,87 @@ def test_two_solves_are_bit_identical(amd):
     a, b = amd.solve(batch), amd.solve(batch)
     M = batch.M
     assert (a.cost[:, :, :M + 1] == b.cost[:, :, :M + 1]).all() and (a.arg[:, :, :M + 1] == b.arg[:, :, :M + 1]).all()
+
+
+def _same_tables(a, b, M):
+    return bool((a.cost[:, :, :M + 1] == b.cost[:, :, :M + 1]).all() and (a.arg[:, :, :M + 1] == b.arg[:, :, :M + 1]).all())
+
+
+@pytest.mark.parametrize("which", ["cfg2", "wide"])
+def test_tables_do_not_depend_on_the_schedule(amd, oracle_mod, which):
+    """The same input under every work order the library can take: one stream or 2, 3, 4 groups of
+    chains (the library's helper streams or the caller's), and 1, 2 or 4 waves per list of splits
+    in the block-product kernel.  Every variant must give the tables of the plain call, bit for bit
+    (and those equal the oracle's, checked on one chain)."""
+    import torch
+    batch = make_config(2) if which == "cfg2" else \
+        random_chain_batch(32, 30000, 5, 35, size_hi=1000, time_hi=5000, overheads=True)
+    M = batch.M
+    amd.ckpt_init()
+    base = amd.solve(batch)
+    assert_tables_equal(oracle_mod, batch, base, nthreads=8, chains=[batch.B - 1])
+    own = [torch.cuda.Stream() for _ in range(3)]
+    variants = [dict(groups=1), dict(groups=2), dict(groups=3), dict(groups=4),
+                dict(groups=1, list_split=1), dict(groups=1, list_split=2), dict(groups=1, list_split=4),
+                dict(groups=4, list_split=2), dict(groups=2, list_split=4),
+                dict(groups=4, side_streams=[s.cuda_stream for s in own]),
+                dict(groups=3, list_split=1, side_streams=[s.cuda_stream for s in own[:2]])]
+    for opts in variants:
+        print(f"case {batch.name} {opts}", flush=True)
+        other = amd.solve(batch, **opts)
+        torch.cuda.synchronize()
+        assert _same_tables(base, other, M), opts
+
+
+def test_solve_with_other_streams_busy(amd, oracle_mod):
+    """A split solve issued while streams of the process that the library does not know are busy
+    with copies and kernels of their own."""
+    import torch
+    batch = random_chain_batch(32, 30000, 5, 38, size_hi=1000, time_hi=5000, overheads=True)
+    busy = [torch.cuda.Stream() for _ in range(3)]
+    blobs = [torch.zeros(1 << 24, dtype=torch.int32, device="cuda") for _ in busy]
+    for _ in range(20):
+        for st, blob in zip(busy, blobs):
+            with torch.cuda.stream(st):
+                blob.add_(1)
+                blob.copy_(blob.flip(0))
+    sol = amd.solve(batch, check=False)
+    for st, blob in zip(busy, blobs):
+        with torch.cuda.stream(st):
+            blob.add_(1)
+    torch.cuda.synchronize()
+    assert_tables_equal(oracle_mod, batch, sol, nthreads=8)
+    assert all(int(blob[0]) == 21 for blob in blobs)
+
+
+def test_capture_of_a_long_chain_on_a_split_batch(amd):
+    """L >= 157 (the frontier kernel needs its enlarged on-chip allocation) on a batch large
+    enough to be split, captured after ckpt_init and replayed against the eager tables."""
+    import torch
+    batch = random_chain_batch(160, 2500, 4, 39, size_hi=60, time_hi=3000)
+    L, M, B = batch.L, batch.M, batch.B
+    amd.ckpt_init()
+    up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    uf, ub, wa, wabar = up(batch.uf), up(batch.ub), up(batch.wa), up(batch.wabar)
+    cost = torch.empty(amd.ckpt_table_elems(L, M, B), dtype=torch.int32, device="cuda")
+    arg = torch.empty(amd.ckpt_table_elems(L, M, B), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(amd.ckpt_workspace_bytes(L, M, B), dtype=torch.uint8, device="cuda")
+    eager = amd.solve(batch)
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        amd.ckpt_solve_batched(uf, ub, wa, wabar, L, M, B, cost, arg, ws)
+    torch.cuda.synchronize()
+    pitch = amd.ckpt_row_pitch(M)
+    for _ in range(2):
+        cost.fill_(-5)
+        arg.fill_(77)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert (cost.view(B, -1, pitch)[:, :, :M + 1] == eager.cost[:, :, :M + 1]).all()
+        assert (arg.view(B, -1, pitch)[:, :, :M + 1] == eager.arg[:, :, :M + 1]).all()
 
 
 def test_schedule_from_gpu_table_runs_in_budget(amd, oracle_mod):
@@ -253,3 +340,47 @@ def test_cfg4_infeasible_share(amd):
     frac = n_inf / (batch.B * amd.ckpt_table_rows(batch.L) * (batch.M + 1))
     assert abs(frac - 0.30) < 0.01, frac
     _full.clear()
+
+
+def test_split_requested_inside_a_capture_without_init_is_refused():
+    """Nothing is created behind a capture: a fresh process that asks for a split solve while its
+    stream is being captured, without ckpt_init, gets CKPT_E_NOTREADY and a capture that still
+    ends normally; after ckpt_init the same capture succeeds.  Runs in a process of its own
+    because the helper streams of this one may exist already."""
+    import os
+    import subprocess
+    import sys
+    code = r'''
+import numpy as np, torch, sys
+sys.path.insert(0, %r)
+import paper_2302_02599_amd as amd
+from workloads import make_config
+batch = make_config(2)
+L, M, B = batch.L, batch.M, batch.B
+up = lambda a: torch.from_numpy(np.ascontiguousarray(a)).cuda()
+uf, ub, wa, wabar = up(batch.uf), up(batch.ub), up(batch.wa), up(batch.wabar)
+cost = torch.empty(amd.ckpt_table_elems(L, M, B), dtype=torch.int32, device="cuda")
+arg = torch.empty(amd.ckpt_table_elems(L, M, B), dtype=torch.uint8, device="cuda")
+ws = torch.empty(amd.ckpt_workspace_bytes(L, M, B), dtype=torch.uint8, device="cuda")
+side = torch.cuda.Stream()
+torch.cuda.synchronize()
+codes = []
+for attempt in range(2):
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        try:
+            amd.ckpt_solve_batched_opts(uf, ub, wa, wabar, L, M, B, cost, arg, ws, groups=2)
+            codes.append(0)
+        except amd.CkptError as e:
+            codes.append(e.code)
+    torch.cuda.synchronize()
+    if attempt == 0:
+        amd.ckpt_init()
+graph.replay()
+torch.cuda.synchronize()
+ref = amd.solve(batch, groups=1)
+ok = bool((cost.view(B, -1, amd.ckpt_row_pitch(M))[:, :, :M + 1] == ref.cost[:, :, :M + 1]).all())
+print("RESULT", codes, ok)
+''' % os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    out = subprocess.run([sys.executable, "-c", code], capture_output=True, text=True, timeout=300)
+    assert "RESULT [-8, 0] True" in out.stdout, out.stdout[-2000:] + out.stderr[-2000:]

@@ -152,6 +152,88 @@ def test_schedule_batched_small_capacity_and_corrupt_table(amd, solved):
     assert got[3] == -7 and all(v > 0 for k, v in enumerate(got) if k != 3)
 
 
+def _walk_on_device(amd, batch, sol, budgets):
+    import torch
+    L, M, B = batch.L, batch.M, batch.B
+    cap = L * (L + 1) // 2 + L
+    ws = torch.empty(amd.ckpt_schedule_workspace_bytes(L, B), dtype=torch.uint8, device="cuda")
+    ops = torch.zeros((B, cap, 2), dtype=torch.uint8, device="cuda")
+    n_ops = torch.zeros(B, dtype=torch.int32, device="cuda")
+    amd.ckpt_schedule_batched(sol.arg, torch.from_numpy(batch.wa).cuda(), torch.from_numpy(batch.wabar).cuda(), L, M, B,
+                              torch.tensor(budgets, dtype=torch.int32, device="cuda"), ops, cap, n_ops, ws)
+    return ops, cap, n_ops
+
+
+def _check_block_indices(amd, oracle_mod, batch, sol, budgets, name):
+    """Device block indices of every chain against the oracle's, computed from the oracle-checked
+    operation list of the same chain."""
+    import torch
+    L, B = batch.L, batch.B
+    ops, cap, n_ops = _walk_on_device(amd, batch, sol, budgets)
+    blocks = torch.full((B, L), -9, dtype=torch.int32, device="cuda")
+    n_blocks = torch.full((B,), -9, dtype=torch.int32, device="cuda")
+    amd.ckpt_block_indices_batched(ops, cap, n_ops, L, B, blocks, n_blocks)
+    ops_h, n_h, blocks_h, nb_h = ops.cpu().numpy(), n_ops.cpu().tolist(), blocks.cpu().tolist(), n_blocks.cpu().tolist()
+    shapes = set()
+    for b in range(B):
+        if n_h[b] < 0:
+            assert nb_h[b] == n_h[b] and blocks_h[b] == [-1] * L, (name, b)
+            continue
+        want, want_n = oracle_mod.block_indices([tuple(x) for x in ops_h[b, :n_h[b]].tolist()], L)
+        assert (blocks_h[b], nb_h[b]) == (want, want_n), (name, b)
+        shapes.add(tuple(want))
+    return shapes
+
+
+def test_block_indices_batched(amd, oracle_mod, solved):
+    batch, sol, tables = solved
+    shapes = set()
+    for name, budgets in _budget_sets(batch, tables, oracle_mod):
+        shapes |= _check_block_indices(amd, oracle_mod, batch, sol, budgets, name)
+    assert len(shapes) > 4
+
+
+def test_block_indices_batched_many_chains_and_long_chains(amd, oracle_mod):
+    """700 chains (more than any block has threads), and chains longer than one pass of 64 stages
+    with tight budgets so that blocks straddle the passes."""
+    from workloads.chains import random_chain_batch
+    rng = np.random.default_rng(11)
+    batch = random_chain_batch(10, 100, 700, 34, size_hi=9)
+    sol = amd.solve(batch)
+    shapes = _check_block_indices(amd, oracle_mod, batch, sol, rng.integers(-1, 101, 700).tolist(), "many")
+    assert len(shapes) > 20
+    batch = random_chain_batch(150, 400, 3, 42, size_hi=9, time_hi=900)
+    sol = amd.solve(batch)
+    cost_h = sol.cost[:, amd.ckpt_row_index(150, 1, 150), :401].cpu().numpy()
+    first = [int(np.argmax(cost_h[b] < amd.CKPT_INF)) for b in range(3)]
+    for name, budgets in (("tightest", first), ("tight", [f + 9 for f in first]), ("roomy", [400] * 3)):
+        shapes = _check_block_indices(amd, oracle_mod, batch, sol, budgets, name)
+        if name == "tightest":
+            assert any(max(sh) >= 1 and sum(1 for v in sh if v >= 0) > 64 for sh in shapes)
+
+
+def test_block_indices_batched_rejects_edited_lists(amd, solved):
+    import torch
+    batch, sol, _ = solved
+    L, M, B = batch.L, batch.M, batch.B
+    ops, cap, n_ops = _walk_on_device(amd, batch, sol, [M // 3] * B)
+    ops_h = ops.cpu().numpy().copy()
+    ops_h[1, 0] = (2, 1)                  # chain 1: F_null^1 has no block to continue
+    ops_h[2, 5, 1] = 9                    # chain 2: stage out of order in the first sweep
+    ops_h[3, L] = (0, L)                  # chain 3: no B^L after the first sweep
+    n_h = n_ops.cpu().numpy().copy()
+    n_h[4] = L                            # chain 4: list shorter than the chain
+    n_h[5] = cap + 1                      # chain 5: longer than the buffer
+    n_h[6] = -3                           # chain 6: the walk had failed
+    blocks = torch.full((B, L), -9, dtype=torch.int32, device="cuda")
+    n_blocks = torch.full((B,), -9, dtype=torch.int32, device="cuda")
+    amd.ckpt_block_indices_batched(torch.from_numpy(ops_h).cuda(), cap, torch.from_numpy(n_h).cuda(), L, B, blocks,
+                                   n_blocks)
+    got = n_blocks.cpu().tolist()
+    assert got[1:7] == [-7, -7, -7, -7, -1, -3] and got[0] >= 0 and got[7] >= 0
+    assert (blocks[1:7] == -1).all()
+
+
 def _simulate_on_device(amd, batch, ops, cap, n_ops):
     import torch
     up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a, dtype=np.int32)).cuda()
