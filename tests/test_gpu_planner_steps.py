@@ -216,7 +216,7 @@ def test_block_indices_batched_rejects_edited_lists(amd, solved):
     import torch
     batch, sol, _ = solved
     L, M, B = batch.L, batch.M, batch.B
-    ops, cap, n_ops = _walk_on_device(amd, batch, sol, [M // 3] * B)
+    ops, cap, n_ops = _walk_on_device(amd, batch, sol, [M] * B)
     ops_h = ops.cpu().numpy().copy()
     ops_h[1, 0] = (2, 1)                  # chain 1: F_null^1 has no block to continue
     ops_h[2, 5, 1] = 9                    # chain 2: stage out of order in the first sweep
