@@ -162,6 +162,24 @@ int ckpt_solve_batched_opts(const ckpt_chains_t* chains, int L, int M, int B, vo
                             uint8_t* arg, void* workspace, const ckpt_solve_opts_t* opts);
 
 /*
+ * ckpt_solve_batched for callers that cannot allocate or bring a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  The workspace is a
+ * fixed array of CKPT_NOALLOC_MAX_WORKSPACE bytes inside the library's device code, one copy
+ * per GPU, held until the process ends.  The call allocates nothing and creates nothing (the
+ * batch is split over the helper streams only if ckpt_init has made them); its very first
+ * use on a device resolves the array's address, so call ckpt_init once beforehand if that
+ * first use would fall inside a stream capture.  Every call on one GPU uses the same array:
+ * calls that overlap in time on one GPU race -- serialise them (one stream, or events).
+ * The tables are those of ckpt_solve_batched, bit for bit.  ckpt_check_inputs with
+ * workspace = NULL reads the flags of the most recent such solve on the current device.
+ * Returns as ckpt_solve_batched, plus CKPT_E_LIMIT when ckpt_workspace_bytes(L, M, B) exceeds
+ * CKPT_NOALLOC_MAX_WORKSPACE.
+ */
+#define CKPT_NOALLOC_MAX_WORKSPACE (16u << 20)
+int ckpt_solve_batched_noalloc(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
+                               uint8_t* arg);
+
+/*
  * Measurement aid: the same fill as ckpt_solve_batched, with a HIP event recorded on
  * the stream after every kernel launch.  The call waits for the stream, then adds the
  * elapsed time between consecutive events to the kernel kind launched in between
@@ -177,7 +195,8 @@ int ckpt_solve_profiled(const ckpt_chains_t* chains, int L, int M, int B, void* 
 const char* ckpt_kernel_name(int kind);
 
 /*
- * After ckpt_solve_batched on the same stream: wait for the stream and copy the
+ * After ckpt_solve_batched on the same stream (workspace = the one it was given; NULL = the
+ * static one of ckpt_solve_batched_noalloc): wait for the stream and copy the
  * per-chain input flags (0 = chain met the value preconditions) into flags_host[B]
  * (HOST memory).  Returns CKPT_OK, CKPT_E_INPUT if any flag is nonzero (the
  * tables of such a chain are unspecified, all memory accesses stayed in bounds),

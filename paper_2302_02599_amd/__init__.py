@@ -9,5 +9,5 @@ from .binding import (CKPT_INF, CkptError, Solution, ckpt_block_indices, ckpt_bl
                       ckpt_budget_sweep, ckpt_check_inputs, ckpt_discretize, ckpt_discretize_sweep, ckpt_init,
                       ckpt_linearize, ckpt_row_index, ckpt_row_pitch, ckpt_schedule, ckpt_schedule_batched,
                       ckpt_schedule_workspace_bytes, ckpt_select_plan, ckpt_simulate_batched, ckpt_solve_batched,
-                      ckpt_solve_batched_opts, ckpt_solve_profiled, ckpt_table_elems, ckpt_table_rows,
+                      ckpt_solve_batched_noalloc, ckpt_solve_batched_opts, ckpt_solve_profiled, ckpt_table_elems, ckpt_table_rows,
                       ckpt_workspace_bytes, lib_path, load_library, solve)

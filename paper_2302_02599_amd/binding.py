@@ -67,6 +67,8 @@ def load_library():
     lib.ckpt_solve_batched_opts.restype = i
     lib.ckpt_solve_batched_opts.argtypes = [ctypes.POINTER(_Chains), i, i, i, vp, vp, vp, vp,
                                             ctypes.POINTER(_SolveOpts)]
+    lib.ckpt_solve_batched_noalloc.restype = i
+    lib.ckpt_solve_batched_noalloc.argtypes = [ctypes.POINTER(_Chains), i, i, i, vp, vp, vp]
     lib.ckpt_block_indices.restype = i
     lib.ckpt_block_indices.argtypes = [ctypes.POINTER(_Op), i, i, vp]
     lib.ckpt_block_indices_batched.restype = i
@@ -199,12 +201,29 @@ def ckpt_solve_batched_opts(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, *,
         raise CkptError(rc, "ckpt_solve_batched_opts")
 
 
+def ckpt_solve_batched_noalloc(uf, ub, wa, wabar, L, M, B, cost, arg, *, wdelta=None, of=None, ob=None,
+                               stream=None) -> None:
+    """ckpt_solve_batched on the library's static per-GPU workspace: allocates nothing."""
+    import torch
+    ch = _Chains(_dev_ptr(uf, "uf", (B, L)), _dev_ptr(ub, "ub", (B, L)), _dev_ptr(wa, "wa", (B, L + 1)),
+                 _dev_ptr(wabar, "wabar", (B, L)), _dev_ptr(wdelta, "wdelta", (B, L + 1)),
+                 _dev_ptr(of, "of", (B, L)), _dev_ptr(ob, "ob", (B, L)))
+    n = ckpt_table_elems(L, M, B)
+    if n and (cost.numel() < n or arg.numel() < n or cost.dtype != torch.int32 or arg.dtype != torch.uint8):
+        raise ValueError("cost/arg tables too small or of the wrong dtype")
+    rc = load_library().ckpt_solve_batched_noalloc(ctypes.byref(ch), L, M, B, _stream(stream), cost.data_ptr(),
+                                                   arg.data_ptr())
+    if rc != 0:
+        raise CkptError(rc, "ckpt_solve_batched_noalloc")
+
+
 def ckpt_check_inputs(workspace, L, M, B, *, stream=None) -> np.ndarray:
-    """Synchronise and return the per-chain input flags (all zero = fine); raises on nonzero."""
+    """Synchronise and return the per-chain input flags (all zero = fine); raises on nonzero.
+    workspace None: the static workspace of ckpt_solve_batched_noalloc."""
     import torch
     flags = np.zeros(B, np.int32)
     st = torch.cuda.current_stream().cuda_stream if stream is None else stream
-    rc = load_library().ckpt_check_inputs(workspace.data_ptr(), L, M, B, ctypes.c_void_p(st),
+    rc = load_library().ckpt_check_inputs(None if workspace is None else workspace.data_ptr(), L, M, B, ctypes.c_void_p(st),
                                           flags.ctypes.data)
     if rc not in (0, -6):
         raise CkptError(rc, "ckpt_check_inputs")

@@ -957,14 +957,21 @@ struct Profile {
 //            gets by default (more streams than that share queues and serialise: six or eight
 //            groups measured slower than one).  Created by ckpt_init or by the first solve
 //            that wants to split, never while that solve's stream is being captured.
+//   scratch  the device address of this GPU's copy of the static workspace below.
 constexpr int kSideStreams = 3;
 struct Device {
     hipStream_t stream[kSideStreams] = {};
     hipEvent_t join[kSideStreams] = {};
     hipEvent_t fork = nullptr;
     bool helpers_tried = false, helpers_ok = false;
+    void* scratch = nullptr;
     std::mutex busy;  // one fork/join sequence at a time per device
 };
+
+// Workspace of ckpt_solve_batched_noalloc, for callers that cannot allocate: a fixed array in
+// every GPU's copy of the code object, held until the process ends.  In host code the array's
+// name is only a handle for hipGetSymbolAddress; kernels are given the resolved address.
+static __device__ __align__(256) unsigned char g_scratch[CKPT_NOALLOC_MAX_WORKSPACE];
 
 std::mutex g_devices_lock;
 Device g_devices[64];
@@ -987,6 +994,17 @@ bool ensure_helpers(Device& d) {
         d.helpers_ok = ok;
     }
     return d.helpers_ok;
+}
+
+// Resolves this device's address of g_scratch once (the device must be current).
+void* ensure_scratch(Device& d) {
+    std::lock_guard<std::mutex> guard(g_devices_lock);
+    if (!d.scratch) {
+        void* p = nullptr;
+        if (!hip_ok(hipGetSymbolAddress(&p, HIP_SYMBOL(g_scratch))) || !p) return nullptr;
+        d.scratch = p;
+    }
+    return d.scratch;
 }
 
 bool helpers_ready(Device& d) {
@@ -1176,7 +1194,7 @@ int ckpt_init(int device) {
     if (device >= 64) return CKPT_E_LIMIT;
     if (device != prev && !hip_ok(hipSetDevice(device))) return CKPT_E_HIP;
     Device& d = g_devices[device];
-    const bool ok = ensure_helpers(d) && allow_frontier_lds();
+    const bool ok = ensure_helpers(d) && ensure_scratch(d) != nullptr && allow_frontier_lds();
     if (device != prev && !hip_ok(hipSetDevice(prev))) return CKPT_E_HIP;
     return ok ? CKPT_OK : CKPT_E_HIP;
 }
@@ -1184,6 +1202,18 @@ int ckpt_init(int device) {
 int ckpt_solve_batched(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
                        uint8_t* arg, void* workspace) {
     return solve_impl(chains, L, M, B, stream, cost, arg, workspace, nullptr, nullptr, true);
+}
+
+int ckpt_solve_batched_noalloc(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
+                               uint8_t* arg) {
+    if (int rc = check_dims(L, M, B)) return rc;
+    if (ckpt_workspace_bytes(L, M, B) > CKPT_NOALLOC_MAX_WORKSPACE) return CKPT_E_LIMIT;
+    Device* dev = current_device();
+    if (!dev) return CKPT_E_HIP;
+    void* scratch = ensure_scratch(*dev);
+    if (!scratch) return CKPT_E_HIP;
+    // creates nothing: the batch is split only if the helper streams exist already
+    return solve_impl(chains, L, M, B, stream, cost, arg, scratch, nullptr, nullptr, false);
 }
 
 int ckpt_solve_batched_opts(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
@@ -1223,8 +1253,14 @@ const char* ckpt_kernel_name(int kind) {
 }
 
 int ckpt_check_inputs(const void* workspace, int L, int M, int B, void* stream, int32_t* flags_host) {
-    if (!workspace || !flags_host) return CKPT_E_ARG;
+    if (!flags_host) return CKPT_E_ARG;
     if (int rc = check_dims(L, M, B)) return rc;
+    if (!workspace) {  // the static workspace of ckpt_solve_batched_noalloc on the current device
+        if (ckpt_workspace_bytes(L, M, B) > CKPT_NOALLOC_MAX_WORKSPACE) return CKPT_E_LIMIT;
+        Device* dev = current_device();
+        workspace = dev ? ensure_scratch(*dev) : nullptr;
+        if (!workspace) return CKPT_E_HIP;
+    }
     const Workspace ws = carve(const_cast<void*>(workspace), L, B);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (!hip_ok(hipMemcpyAsync(flags_host, ws.flags, size_t(B) * sizeof(int32_t), hipMemcpyDeviceToHost, st)))
