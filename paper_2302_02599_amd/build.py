@@ -8,7 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libckpt_dp.so")
-SOURCES = ["ckpt_dp.hip", "ckpt_schedule.cpp", "ckpt_linearize.cpp"]
+SOURCES = ["ckpt_dp.hip", "ckpt_host.cpp", "ckpt_schedule.cpp", "ckpt_linearize.cpp"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC", "-fno-honor-nans",
