@@ -1,18 +1,33 @@
 #!/usr/bin/env python3
 """Benchmark of the batched activation-checkpoint DP on one MI355X.
 
-One "step" = one pass of the whole hot path (threshold precompute + full table fill of
-every chain of the batch) with the chain descriptors already resident in HBM.  Prints
-ONE JSON line: min-plus candidate evaluations per second on the named workload, DP
-cells per second, the roofline of the dominant kernel (durations from HIP events
-recorded by the library on the launch stream) and the CPU oracle timed on a bounded
-sample of the same workload.
+One "step" = one pass of the whole hot path (threshold precompute, feasibility frontier and the
+full table fill of every chain of the batch) with the chain descriptors already resident in HBM.
+Prints ONE JSON line:
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu] [--all] [--calib-copy MIB]
+  value / ms_per_step   K solves enqueued back to back between two synchronisations (the
+                        pipelined mean: the host's launch work hides behind the previous solve)
+  latency_ms            every solve timed on its own with HIP events on the launch stream, after
+                        3 warm-ups: median, min, max of >= 10 solves
+  roofline              of the kernel that takes most of a solve.  `achieved` = bytes that the
+                        kernel's waves really ask the memory system for (counted on the device:
+                        work skipped by the feasibility tests is not billed) / its launch time
+                        from HIP events; `traffic` = HBM bytes per launch from the committed
+                        rocprofv3 counter summary; `method_floor` = what the method itself needs
+                        (5 bytes per cell stored once, 2 vector operations per candidate)
+  measured_roofs        copy bandwidth, Infinity-Cache read bandwidth, the block-product kernel's
+                        access pattern without arithmetic, register-only candidate rates
+  other_workloads       the L = 96, B = 64 workload with the same figures
+  cpu_baseline          the CPU oracle on a bounded sample of the same workload
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu] [--all] [--roofs]
+                  [--calib-copy MIB] [--groups G] [--row-launches 0|1] [--list-split 0|1|2|4]
 """
 import argparse
+import ctypes
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -24,14 +39,10 @@ sys.path.insert(0, ROOT)
 # vector peak counts an FMA as two), and so do 32-bit integer operations.
 PEAK_HBM = 8.0e12
 PEAK_VALU_OPS = 256 * 64 * 2.4e9
-# Algorithmic work of gemm_kernel per candidate of the middle splits: 16 operand rows of 4 B feed
-# an 8x8 tile of cells, i.e. 1 byte of table reads per candidate; one float64 add and one float64
-# min per candidate.  Every cell of the tile costs 5 bytes stored (cost + candidate number: the
-# partial result for rows 0..6, the finished cell for row 7), and row 7, which the kernel finishes
-# itself, one 4-byte operand load per split in the column block and per C_all.
-GEMM_BYTES_PER_EVAL = 1.0
-GEMM_BYTES_PER_CELL = 5.0
-GEMM_OPS_PER_EVAL = 2
+# What the method itself needs, whatever the kernel design: every cell is stored once (4-byte cost
+# + 1-byte candidate number), and every candidate takes one add and one min / compare.
+FLOOR_BYTES_PER_CELL = 5.0
+FLOOR_OPS_PER_EVAL = 2
 
 
 def counts(L, M, B):
@@ -40,55 +51,15 @@ def counts(L, M, B):
     return cells, evals
 
 
-def row_loads(L, T, D, I, r):
-    """(operand loads, stored cells) of one lane finishing row r of tile (I, I + D): 9 loads per
-    split in the row block (left + 8 right; clamped columns are loaded too), one per split in the
-    column block, one C_all operand per cell with j > i."""
-    J, i = I + D, I * T + r
-    cols = [j for j in range(J * T, min(L, J * T + T)) if j >= i]
-    near_i = 0 if D == 0 else ((T - r) if D == 1 else (T - 1 - r))
-    loads = near_i * (1 + T)
-    loads += sum(1 for j in cols for q in range(max(i + 1, J * T + 1), j + 1))
-    loads += sum(1 for j in cols if j > i)
-    return loads, len(cols)
-
-
-def gemm_work(L, M, B, T=8):
-    """(middle candidates, cells, row-7 operand loads) of gemm_kernel per step: for every tile of
-    block diagonal D >= 2 the splits strictly between its row block and its column block, plus
-    the first stage of the column block; and the loads with which it finishes row 7.  Nominal
-    counts: candidates that the feasibility test drops still count, as infeasible cells do in
-    the headline metric."""
+def gemm_evals(L, M, B, T=8):
+    """Nominal candidates of the block-product kernel per step: for every tile of block diagonal
+    D >= 2 the splits between its row block and its column block."""
     nblk = (L + T - 1) // T
-    evals = cells = loads7 = 0
+    evals = 0
     for D in range(2, nblk):
         for I in range(nblk - D):
-            cols = min(T, L - (I + D) * T)
-            cells += T * cols
-            evals += T * cols * ((D - 1) * T + 1)
-            loads7 += row_loads(L, T, D, I, T - 1)[0]
-    return evals * (M + 1) * B, cells * (M + 1) * B, loads7 * (M + 1) * B
-
-
-def gemm_bytes(L, M, B, T=8):
-    evals, cells, loads7 = gemm_work(L, M, B, T)
-    return GEMM_BYTES_PER_EVAL * evals + GEMM_BYTES_PER_CELL * cells + 4 * loads7
-
-
-def row_bytes(L, M, B, T=8):
-    """Algorithmic bytes of all row_kernel launches of a step (nominal: waves that the frontier
-    test skips still count): 4 bytes per operand load, 5 bytes per cell of gemm partial (D >= 2)
-    and 5 bytes stored per cell.  Row 7 of the tiles of D >= 2 belongs to gemm_kernel."""
-    nblk = (L + T - 1) // T
-    total = 0
-    for D in range(nblk):
-        for I in range(nblk - D):
-            for r in range(T):
-                if I * T + r >= L or (D >= 2 and r == T - 1):
-                    continue
-                loads, stored = row_loads(L, T, D, I, r)
-                total += 4 * loads + (5 * T if D >= 2 else 0) + 5 * stored
-    return total * (M + 1) * B
+            evals += T * min(T, L - (I + D) * T) * ((D - 1) * T + 1)
+    return evals * (M + 1) * B
 
 
 def measured_traffic(workload, kernel):
@@ -114,10 +85,21 @@ def upload(batch, dev):
                 wdelta=up(batch.wdelta), of=up(batch.of), ob=up(batch.ob))
 
 
-def run_config(amd, idx, steps, warmup, dev, profile=True):
+def first_chains(batch, n):
+    """The first n chains of a workload as a batch of their own (the planner's small-batch case)."""
+    import dataclasses
+    cut = lambda a: None if a is None else a[:n]
+    return dataclasses.replace(batch, name=f"{batch.name}_first{n}", B=n, uf=cut(batch.uf), ub=cut(batch.ub),
+                               wa=cut(batch.wa), wabar=cut(batch.wabar), wdelta=cut(batch.wdelta), of=cut(batch.of),
+                               ob=cut(batch.ob))
+
+
+def run_config(amd, idx, steps, warmup, dev, profile=True, solves=10, sched=None, chains=None):
     import torch
     from workloads import make_config
     batch = make_config(idx)
+    if chains:
+        batch = first_chains(batch, chains)
     L, M, B = batch.L, batch.M, batch.B
     t = upload(batch, dev)
     rows, pitch = amd.ckpt_table_rows(L), amd.ckpt_row_pitch(M)
@@ -125,9 +107,13 @@ def run_config(amd, idx, steps, warmup, dev, profile=True):
     arg = torch.empty((B, rows, pitch), dtype=torch.uint8, device=dev)
     ws = torch.empty(amd.ckpt_workspace_bytes(L, M, B), dtype=torch.uint8, device=dev)
     opt = dict(wdelta=t["wdelta"], of=t["of"], ob=t["ob"])
+    amd.ckpt_init()
 
     def step():
-        amd.ckpt_solve_batched(t["uf"], t["ub"], t["wa"], t["wabar"], L, M, B, cost, arg, ws, **opt)
+        if sched:
+            amd.ckpt_solve_batched_opts(t["uf"], t["ub"], t["wa"], t["wabar"], L, M, B, cost, arg, ws, **opt, **sched)
+        else:
+            amd.ckpt_solve_batched(t["uf"], t["ub"], t["wa"], t["wabar"], L, M, B, cost, arg, ws, **opt)
 
     for _ in range(warmup):
         step()
@@ -139,22 +125,125 @@ def run_config(amd, idx, steps, warmup, dev, profile=True):
     wall = time.perf_counter() - t0
     flags = amd.ckpt_check_inputs(ws, L, M, B)
     assert not flags.any(), flags
+    # every solve on its own: events on the launch stream (the solve forks from and joins into it)
+    lat = []
+    for k in range(3 + max(1, solves)):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        step()
+        e1.record()
+        e1.synchronize()
+        if k >= 3:
+            lat.append(e0.elapsed_time(e1))
     kinds = None
     if profile:
         acc = {}
-        for _ in range(max(1, min(steps, 5))):
-            for name, (ms, n) in amd.ckpt_solve_profiled(t["uf"], t["ub"], t["wa"], t["wabar"], L, M, B, cost,
-                                                         arg, ws, **opt).items():
-                a = acc.setdefault(name, [0.0, 0, 0])
-                a[0] += ms; a[1] += n; a[2] += 1
-        kinds = {k: dict(ms_per_step=v[0] / v[2], launches_per_step=v[1] // v[2]) for k, v in acc.items()}
+        reps = max(1, min(steps, 5))
+        for r in range(reps):
+            res = amd.ckpt_solve_profiled(t["uf"], t["ub"], t["wa"], t["wabar"], L, M, B, cost, arg, ws,
+                                          count_bytes=(r == 0), **opt)
+            for name, v in res.items():
+                a = acc.setdefault(name, [0.0, 0, 0.0, 0.0])
+                a[0] += v[0]; a[1] += v[1]
+                if len(v) == 4:
+                    a[2], a[3] = v[2], v[3]
+        kinds = {k: dict(ms_per_step=v[0] / reps, launches_per_step=v[1] // reps, bytes_loaded_per_step=v[2],
+                         bytes_stored_per_step=v[3]) for k, v in acc.items()}
     cells, evals = counts(L, M, B)
-    return dict(batch=batch, ms=wall / steps * 1e3, cells=cells, evals=evals, kinds=kinds)
+    return dict(batch=batch, ms=wall / steps * 1e3, cells=cells, evals=evals, kinds=kinds,
+                latency={"median": statistics.median(lat), "min": min(lat), "max": max(lat), "solves": len(lat)})
+
+
+def roofline_of(r):
+    """Roofline object of the kernel that takes most of a solve (block product or rows)."""
+    batch, kinds = r["batch"], r["kinds"]
+    dom = max(("gemm_kernel", "tile_rows_kernel"), key=lambda k: kinds[k]["ms_per_step"])
+    k = kinds[dom]
+    launches = max(1, k["launches_per_step"])
+    per_launch_s = k["ms_per_step"] * 1e-3 / launches
+    moved = (k["bytes_loaded_per_step"] + k["bytes_stored_per_step"]) / launches
+    g_evals = gemm_evals(batch.L, batch.M, batch.B)
+    if dom == "gemm_kernel":
+        dom_evals, ops_per_eval = g_evals, 2
+        alu_unit = "Tlane-op/s (float64 add + min per candidate, nominal candidate count)"
+    else:
+        dom_evals, ops_per_eval = r["evals"] - g_evals, 4
+        alu_unit = "Tlane-op/s (32-bit add, compare, two selects per candidate, nominal candidate count)"
+    step_s = r["ms"] * 1e-3
+    floor_bytes = FLOOR_BYTES_PER_CELL * r["cells"]
+    floor_ops = FLOOR_OPS_PER_EVAL * r["evals"]
+    solve_bytes = sum(kinds[n]["bytes_loaded_per_step"] + kinds[n]["bytes_stored_per_step"]
+                      for n in ("gemm_kernel", "tile_rows_kernel"))
+    return {"bound": "hbm", "kernel": dom, "achieved": moved / per_launch_s / 1e9, "peak": PEAK_HBM / 1e9,
+            "unit": "GB/s", "frac": moved / per_launch_s / PEAK_HBM,
+            "traffic": measured_traffic(batch.name, dom),
+            "requested_bytes_per_launch": moved, "avg_launch_ms": per_launch_s * 1e3, "launches_per_step": launches,
+            "counted": "bytes the kernel's waves ask for (256 per wave and load, 320 per wave and stored cell), "
+                       "counted on the device; work skipped by the feasibility tests is not billed",
+            "alu": {"achieved": ops_per_eval * dom_evals / launches / per_launch_s / 1e12, "peak": PEAK_VALU_OPS / 1e12,
+                    "unit": alu_unit, "frac": ops_per_eval * dom_evals / launches / per_launch_s / PEAK_VALU_OPS},
+            "whole_solve": {"requested_bytes": solve_bytes, "GB/s": solve_bytes / step_s / 1e9,
+                            "frac_of_hbm_peak": solve_bytes / step_s / PEAK_HBM},
+            "method_floor": {"compulsory_bytes": floor_bytes, "hbm_ms": floor_bytes / PEAK_HBM * 1e3,
+                             "alu_ops": floor_ops, "alu_ms": floor_ops / PEAK_VALU_OPS * 1e3,
+                             "solve_over_hbm_floor": step_s / (floor_bytes / PEAK_HBM),
+                             "solve_over_alu_floor": step_s / (floor_ops / PEAK_VALU_OPS),
+                             "note": "5 bytes per cell stored once; one add and one min or compare per candidate"}}
+
+
+def summary_of(r):
+    s = r["ms"] * 1e-3
+    return {"ms_per_step": r["ms"], "evals_per_s": r["evals"] / s, "cells_per_s": r["cells"] / s,
+            "latency_ms": r["latency"], "L": r["batch"].L, "M": r["batch"].M, "B": r["batch"].B}
+
+
+def measure_roofs(dev, quick=True):
+    """Roofs measured on this machine with the microbenchmarks of libckpt_roofs.so."""
+    import torch
+    lib = ctypes.CDLL(os.path.join(ROOT, "paper_2302_02599_amd", "libckpt_roofs.so"))
+    vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+    lib.ckpt_roof_copy.argtypes = [vp, vp, sz, i, vp, vp]
+    lib.ckpt_roof_read.argtypes = [vp, sz, i, vp, vp, vp]
+    lib.ckpt_roof_read_rows.argtypes = [vp, i, i, i, i, vp, vp, vp, vp]
+    lib.ckpt_roof_alu.argtypes = [i, i, i, vp, vp, vp, vp, vp]
+    st = vp(torch.cuda.current_stream().cuda_stream)
+    ms, dbl = ctypes.c_float(), ctypes.c_double()
+    sink = torch.zeros(16, dtype=torch.int32, device=dev)
+    out = {}
+    nbytes = 1 << 30
+    a = torch.zeros(nbytes, dtype=torch.uint8, device=dev)
+    b = torch.empty_like(a)
+    assert lib.ckpt_roof_copy(b.data_ptr(), a.data_ptr(), nbytes, 4, st, ctypes.byref(ms)) == 0
+    out["copy_1GiB"] = {"GB/s_read_plus_write": 2 * 4 * nbytes / ms.value / 1e6}
+    assert lib.ckpt_roof_read(a.data_ptr(), nbytes, 4, sink.data_ptr(), st, ctypes.byref(ms)) == 0
+    out["read_1GiB"] = {"GB/s": 4 * nbytes / ms.value / 1e6}
+    for mib in ((64, 192) if quick else (16, 64, 128, 192, 256, 512)):
+        n = mib << 20
+        reps = max(2, (4 << 30) // n)
+        assert lib.ckpt_roof_read(a.data_ptr(), n, reps, sink.data_ptr(), st, ctypes.byref(ms)) == 0
+        out[f"read_{mib}MiB_repeated"] = {"GB/s": reps * n / ms.value / 1e6, "passes": reps}
+    del b
+    # the block product's access pattern: 4160-column rows, 90 steps, 170 tiles (about 6.5 GB of rows)
+    pitch, nq, tiles = 4160, 90, 170
+    tab = torch.zeros((tiles * 16 * nq + 2) * pitch, dtype=torch.int32, device=dev)
+    for shift in (0, 37):
+        assert lib.ckpt_roof_read_rows(tab.data_ptr(), pitch, nq, tiles, shift, sink.data_ptr(), st, ctypes.byref(ms),
+                                       ctypes.byref(dbl)) == 0
+        out[f"read_16_rows_per_step_shift_{shift}"] = {"GB/s": dbl.value / ms.value / 1e6, "bytes": dbl.value}
+    del tab, a
+    seed = torch.arange(4096, dtype=torch.int32, device=dev) * 2654435
+    blocks, iters = 256 * 4 * 4, 2000
+    res = torch.empty(blocks * 64, dtype=torch.int32, device=dev)
+    for kind, name in ((0, "f64_add_min"), (1, "u32_add_compare_two_selects"), (2, "u32_add_min")):
+        assert lib.ckpt_roof_alu(kind, blocks, iters, seed.data_ptr(), res.data_ptr(), st, ctypes.byref(ms),
+                                 ctypes.byref(dbl)) == 0
+        out[f"register_only_{name}"] = {"Tevals/s": dbl.value / ms.value / 1e9}
+    return out
 
 
 def time_planner_steps(amd, idx, dev, reps=20):
     """Microseconds per call of the planner-side steps on workload idx (tables already filled)."""
-    import numpy as np
     import torch
     from workloads import make_config
     batch = make_config(idx)
@@ -176,10 +265,13 @@ def time_planner_steps(amd, idx, dev, reps=20):
     sim_time = torch.zeros(B, dtype=torch.int64, device=dev)
     sim_peak = torch.zeros(B, dtype=torch.int64, device=dev)
     sim_status = torch.zeros(B, dtype=torch.int32, device=dev)
+    blocks = torch.zeros((B, L), dtype=torch.int32, device=dev)
+    n_blocks = torch.zeros(B, dtype=torch.int32, device=dev)
     steps = {
         "ckpt_select_plan": lambda: amd.ckpt_select_plan(sol.cost, L, M, B, budgets, out),
         "ckpt_schedule_batched": lambda: amd.ckpt_schedule_batched(sol.arg, wa, wabar, L, M, B, budgets, ops, cap,
                                                                    n_ops, ws),
+        "ckpt_block_indices_batched": lambda: amd.ckpt_block_indices_batched(ops, cap, n_ops, L, B, blocks, n_blocks),
         "ckpt_simulate_batched": lambda: amd.ckpt_simulate_batched(uf, ub, wa, wabar, L, B, ops, cap, n_ops, sim_time,
                                                                    sim_peak, sim_status, **extra),
         "ckpt_discretize": lambda: amd.ckpt_discretize(by_wa, by_wabar, budget_bytes, L, M, B, o_wa, o_wabar),
@@ -193,7 +285,7 @@ def time_planner_steps(amd, idx, dev, reps=20):
             fn()
         torch.cuda.synchronize()
         res[name] = (time.perf_counter() - t0) / reps * 1e6
-    assert (o_wa == wa).all() and int(out[0]) >= 0 and int(n_ops.min()) > 0
+    assert (o_wa == wa).all() and int(out[0]) >= 0 and int(n_ops.min()) > 0 and int(n_blocks.min()) >= 0
     root = amd.ckpt_row_index(L, 1, L)
     assert (sim_status == 0).all() and (sim_time == sol.cost[:, root, M]).all() and int(sim_peak.max()) <= M
     return {"workload": batch.name, "us_per_call": res}
@@ -263,7 +355,14 @@ def main():
     ap.add_argument("--calib-copy", type=int, default=0, metavar="MIB",
                     help="first copy MIB mebibytes device to device (reference for rocprofv3 --pmc byte counters)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the cpu_baseline leg")
-    ap.add_argument("--all", action="store_true", help="also time the other four workloads (few steps each)")
+    ap.add_argument("--all", action="store_true", help="also time the other workloads, the planner-side steps, the "
+                                                       "single-chain case and the copy of the tables to the host")
+    ap.add_argument("--roofs", action="store_true", help="full sweep of the roof microbenchmarks")
+    ap.add_argument("--no-roofs", action="store_true", help="skip the roof microbenchmarks")
+    ap.add_argument("--groups", type=int, default=0, help="experiment: chain groups (0 automatic, 1 one stream)")
+    ap.add_argument("--row-launches", type=int, default=0, help="experiment: 1 = one launch per tile row")
+    ap.add_argument("--list-split", type=int, default=0, help="experiment: waves per work list, 0 automatic")
+    ap.add_argument("--stagger", type=int, default=0, help="experiment: phase-shift half of the chain groups")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build solves on one GPU; chains would be split across GPUs with no "
@@ -282,58 +381,45 @@ def main():
         dst.copy_(src)
         torch.cuda.synchronize()
         del src, dst
+    sched = None
+    if a.groups or a.row_launches or a.list_split or a.stagger:
+        sched = dict(groups=a.groups, row_launches=a.row_launches, list_split=a.list_split, stagger=a.stagger)
 
-    r = run_config(amd, a.config, a.steps, a.warmup, dev)
+    r = run_config(amd, a.config, a.steps, a.warmup, dev, sched=sched)
     batch = r["batch"]
-    evals_per_s = r["evals"] / (r["ms"] * 1e-3)
-    kinds = r["kinds"]
-    dom = max(("gemm_kernel", "row_kernel"), key=lambda k: kinds[k]["ms_per_step"])
-    gemm_evals, _, gemm_loads7 = gemm_work(batch.L, batch.M, batch.B)
-    dom_ms = kinds[dom]["ms_per_step"]
-    launches = max(1, kinds[dom]["launches_per_step"])
-    per_launch_s = dom_ms * 1e-3 / launches
-    if dom == "gemm_kernel":
-        alg_bytes = gemm_bytes(batch.L, batch.M, batch.B) / launches
-        dom_evals, ops_per_eval = gemm_evals, GEMM_OPS_PER_EVAL   # the middle splits; row 7 adds < 1 %
-        alu_unit = "Tlane-op/s (float64 add + min per candidate)"
-    else:
-        alg_bytes = row_bytes(batch.L, batch.M, batch.B) / launches
-        dom_evals, ops_per_eval = r["evals"] - gemm_evals - gemm_loads7, 4   # add, compare, two selects each
-        alu_unit = "Tlane-op/s (32-bit add, compare, two selects per candidate)"
-    alg_ops = ops_per_eval * dom_evals / launches
-    roofline = {"bound": "hbm", "kernel": dom, "achieved": alg_bytes / per_launch_s / 1e9, "peak": PEAK_HBM / 1e9,
-                "unit": "GB/s", "frac": alg_bytes / per_launch_s / PEAK_HBM,
-                "traffic": measured_traffic(batch.name, dom),
-                "algorithmic_bytes_per_launch": alg_bytes, "avg_launch_ms": per_launch_s * 1e3,
-                "launches_per_step": launches, "evals_in_kernel_per_step": dom_evals,
-                "alu": {"achieved": alg_ops / per_launch_s / 1e12, "peak": PEAK_VALU_OPS / 1e12,
-                        "unit": alu_unit, "frac": alg_ops / per_launch_s / PEAK_VALU_OPS}}
     out = {
         "metric": "min-plus candidate evaluations per second (whole batch, tables resident in HBM)",
-        "value": evals_per_s, "unit": "evals/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
+        "value": r["evals"] / (r["ms"] * 1e-3), "unit": "evals/s", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": r["ms"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int32", "data": "synthetic",
+        "dtype": "int32",
+        "arith": "float64 keys cost + candidate/256 (exact: integers below 2^34 scaled by 2^-8) in gemm_kernel, "
+                 "uint32 everywhere else; tables int32 cost + uint8 candidate",
+        "data": "synthetic",
         "config": {"workload": batch.name, "L": batch.L, "M": batch.M, "B": batch.B, "cells": r["cells"],
-                   "evals": r["evals"]},
+                   "evals": r["evals"], "counts": "nominal: infeasible cells and candidates skipped by the "
+                                                  "feasibility tests count", "schedule": sched or "automatic"},
         "cells_per_s": r["cells"] / (r["ms"] * 1e-3),
-        "kernels": kinds,
-        "roofline": roofline,
+        "latency_ms": r["latency"],
+        "kernels": r["kinds"],
+        "roofline": roofline_of(r),
     }
+    others = {}
+    if a.config != 3:
+        o = run_config(amd, 3, 10, 3, dev, sched=sched)
+        others[o["batch"].name] = dict(summary_of(o), roofline=roofline_of(o), kernels=o["kinds"])
     if a.all:
-        others = {}
-        for idx in range(5):
-            if idx == a.config:
-                continue
-            o = run_config(amd, idx, 5, 2, dev, profile=False)
-            others[o["batch"].name] = {"ms_per_step": o["ms"], "evals_per_s": o["evals"] / (o["ms"] * 1e-3),
-                                       "cells_per_s": o["cells"] / (o["ms"] * 1e-3)}
-        out["other_workloads"] = others
+        for idx in range(3):
+            if idx != a.config:
+                o = run_config(amd, idx, 20, 3, dev, profile=False, sched=sched)
+                others[o["batch"].name] = summary_of(o)
+        o = run_config(amd, a.config, 20, 3, dev, profile=False, sched=sched, chains=1)
+        others[o["batch"].name] = summary_of(o)
         out["planner_steps"] = time_planner_steps(amd, a.config, dev)
         out["tables_d2h"] = time_d2h(amd, a.config, dev)
-    if not a.no_cpu:
-        out["cpu_baseline"] = cpu_baseline(a.config)
-    else:
-        out["cpu_baseline"] = None
+    out["other_workloads"] = others
+    if not a.no_roofs:
+        out["measured_roofs"] = measure_roofs(dev, quick=not a.roofs)
+    out["cpu_baseline"] = None if a.no_cpu else cpu_baseline(a.config)
     print(json.dumps(out))
 
 

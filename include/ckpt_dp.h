@@ -69,7 +69,8 @@ enum {
     CKPT_E_HIP = -5,        /* a HIP call failed; see ckpt_last_hip_error() */
     CKPT_E_INPUT = -6,      /* ckpt_check_inputs: some chain violates the value preconditions */
     CKPT_E_CORRUPT = -7,    /* the arg table or operation list is not one this library wrote */
-    CKPT_E_NOTREADY = -8    /* helper streams are missing and cannot be created now (stream capture) */
+    CKPT_E_NOTREADY = -8,   /* helper streams are missing and cannot be created now (stream capture) */
+    CKPT_E_INTERNAL = -9    /* ckpt_check_inputs: a bounded wait between work-groups expired; tables incomplete */
 };
 
 /*
@@ -148,6 +149,8 @@ int ckpt_solve_batched(const ckpt_chains_t* chains, int L, int M, int B, void* s
  *                 helper streams.  The fork and join events are the library's in both cases.
  *   list_split    0: automatic.  1, 2 or 4: waves that share one chunk's list of splits in
  *                 every launch of the block-product kernel.
+ *   row_launches  0: the rows of all tiles of a block diagonal are finished by one launch whose
+ *                 work-groups wait for each other's rows.  1: one launch per row of the tiles.
  *   reserved      zeros
  * opts == NULL is ckpt_solve_batched.  Returns as ckpt_solve_batched, plus CKPT_E_NOTREADY
  * when groups > 1 is requested while `stream` is being captured and ckpt_init has not run.
@@ -156,7 +159,9 @@ typedef struct ckpt_solve_opts {
     int groups;
     void* side_streams[3];
     int list_split;
-    int reserved[3];
+    int row_launches;
+    int stagger;
+    int reserved[1];
 } ckpt_solve_opts_t;
 int ckpt_solve_batched_opts(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
                             uint8_t* arg, void* workspace, const ckpt_solve_opts_t* opts);
@@ -180,17 +185,23 @@ int ckpt_solve_batched_noalloc(const ckpt_chains_t* chains, int L, int M, int B,
                                uint8_t* arg);
 
 /*
- * Measurement aid: the same fill as ckpt_solve_batched, with a HIP event recorded on
- * the stream after every kernel launch.  The call waits for the stream, then adds the
- * elapsed time between consecutive events to the kernel kind launched in between
- * (so a kind's time includes the idle gap before each of its launches).
+ * Measurement aid: the same fill as ckpt_solve_batched on one stream, with a HIP event recorded
+ * after every kernel launch.  The call waits for the stream, then adds the elapsed time between
+ * consecutive events to the kernel kind launched in between (so a kind's time includes the
+ * idle gap before each of its launches).
  *   kind_ms, kind_launches   HOST arrays of CKPT_N_KERNEL_KINDS entries, overwritten
- * Creates and destroys events (allocates); not for latency-critical callers.
- * Returns as ckpt_solve_batched.
+ *   kind_bytes               HOST array of 2 * CKPT_N_KERNEL_KINDS doubles or NULL.  If given, the
+ *                            fill runs a second time, untimed, and every wave of the two fill
+ *                            kernels adds up what it asks the memory system for: entry 2k = bytes
+ *                            of table loads of kind k (256 per wave and load), entry 2k + 1 =
+ *                            bytes stored (320 per wave and cell: cost and candidate number).
+ *                            Work that the feasibility tests skip is not counted.
+ * Creates and destroys events and a small device buffer (allocates); not for latency-critical
+ * callers.  Returns as ckpt_solve_batched.
  */
 enum { CKPT_K_PRECOMPUTE = 0, CKPT_K_FRONTIER = 1, CKPT_K_GEMM = 2, CKPT_K_ROW = 3, CKPT_N_KERNEL_KINDS = 4 };
 int ckpt_solve_profiled(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
-                        uint8_t* arg, void* workspace, float* kind_ms, int* kind_launches);
+                        uint8_t* arg, void* workspace, float* kind_ms, int* kind_launches, double* kind_bytes);
 /* Name of a kernel kind as it appears in a rocprofv3 kernel trace; NULL if out of range. */
 const char* ckpt_kernel_name(int kind);
 
@@ -200,7 +211,9 @@ const char* ckpt_kernel_name(int kind);
  * per-chain input flags (0 = chain met the value preconditions) into flags_host[B]
  * (HOST memory).  Returns CKPT_OK, CKPT_E_INPUT if any flag is nonzero (the
  * tables of such a chain are unspecified, all memory accesses stayed in bounds),
- * CKPT_E_ARG or CKPT_E_HIP.  Bits: 1 negative value, 2 time too large, 4 size too large,
+ * CKPT_E_ARG, CKPT_E_HIP, or CKPT_E_INTERNAL if a work-group of the fill gave up waiting for
+ * another one (never seen; every such wait is bounded so that the kernels always end).
+ * Bits: 1 negative value, 2 time too large, 4 size too large,
  * 8 some omega_abar^k below its omega_a^k (the tables of such a chain follow the printed
  * formulas, which are then no longer the optimum over persistent schedules).
  */

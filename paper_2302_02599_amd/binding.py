@@ -36,7 +36,7 @@ class _Op(ctypes.Structure):
 
 class _SolveOpts(ctypes.Structure):
     _fields_ = [("groups", ctypes.c_int), ("side_streams", ctypes.c_void_p * 3), ("list_split", ctypes.c_int),
-                ("reserved", ctypes.c_int * 3)]
+                ("row_launches", ctypes.c_int), ("stagger", ctypes.c_int), ("reserved", ctypes.c_int * 1)]
 
 
 def lib_path() -> str:
@@ -74,7 +74,7 @@ def load_library():
     lib.ckpt_block_indices_batched.restype = i
     lib.ckpt_block_indices_batched.argtypes = [vp, i, vp, i, i, vp, vp, vp]
     lib.ckpt_solve_profiled.restype = i
-    lib.ckpt_solve_profiled.argtypes = [ctypes.POINTER(_Chains), i, i, i, vp, vp, vp, vp, vp, vp]
+    lib.ckpt_solve_profiled.argtypes = [ctypes.POINTER(_Chains), i, i, i, vp, vp, vp, vp, vp, vp, vp]
     lib.ckpt_kernel_name.restype, lib.ckpt_kernel_name.argtypes = ctypes.c_char_p, [i]
     lib.ckpt_check_inputs.restype = i
     lib.ckpt_check_inputs.argtypes = [vp, i, i, i, vp, vp]
@@ -148,8 +148,9 @@ def _marshal(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, wdelta, of, ob, s
 
 
 def ckpt_solve_profiled(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, *, wdelta=None, of=None, ob=None,
-                        stream=None):
-    """Same fill with per-kernel-kind timing; returns {kernel name: (total ms, launches)}. Synchronises."""
+                        stream=None, count_bytes=False):
+    """Same fill on one stream with per-kernel-kind timing; returns {kernel name: (total ms, launches)},
+    with count_bytes {kernel name: (total ms, launches, bytes loaded, bytes stored)}.  Synchronises."""
     lib = load_library()
     ch, st = _marshal(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, wdelta, of, ob, stream)
     n = 0
@@ -157,10 +158,14 @@ def ckpt_solve_profiled(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, *, wde
         n += 1
     ms = (ctypes.c_float * n)()
     cnt = (ctypes.c_int * n)()
+    nbytes = (ctypes.c_double * (2 * n))()
     rc = lib.ckpt_solve_profiled(ctypes.byref(ch), L, M, B, st, cost.data_ptr(), arg.data_ptr(),
-                                 workspace.data_ptr(), ms, cnt)
+                                 workspace.data_ptr(), ms, cnt, nbytes if count_bytes else None)
     if rc != 0:
         raise CkptError(rc, "ckpt_solve_profiled")
+    if count_bytes:
+        return {lib.ckpt_kernel_name(k).decode(): (float(ms[k]), int(cnt[k]), nbytes[2 * k], nbytes[2 * k + 1])
+                for k in range(n)}
     return {lib.ckpt_kernel_name(k).decode(): (float(ms[k]), int(cnt[k])) for k in range(n)}
 
 
@@ -187,12 +192,12 @@ def ckpt_init(device: int = -1) -> None:
 
 
 def ckpt_solve_batched_opts(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, *, groups=0, side_streams=None,
-                            list_split=0, wdelta=None, of=None, ob=None, stream=None) -> None:
+                            list_split=0, row_launches=0, stagger=0, wdelta=None, of=None, ob=None, stream=None) -> None:
     """ckpt_solve_batched with the schedule chosen by the caller: number of chain groups (1 = no
     helper streams), caller-owned side streams (raw hipStream_t values), waves per work list."""
     ch, st = _marshal(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, wdelta, of, ob, stream)
     opts = _SolveOpts()
-    opts.groups, opts.list_split = groups, list_split
+    opts.groups, opts.list_split, opts.row_launches, opts.stagger = groups, list_split, row_launches, stagger
     for k, h in enumerate(side_streams or []):
         opts.side_streams[k] = h
     rc = load_library().ckpt_solve_batched_opts(ctypes.byref(ch), L, M, B, st, cost.data_ptr(), arg.data_ptr(),

@@ -9,6 +9,8 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libckpt_dp.so")
 SOURCES = ["ckpt_dp.hip", "ckpt_host.cpp", "ckpt_schedule.cpp", "ckpt_linearize.cpp"]
+ROOFS_LIB = os.path.join(HERE, "libckpt_roofs.so")
+ROOFS_SOURCES = ["ckpt_roofs.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-shared", "-fPIC", "-fno-honor-nans",
@@ -17,17 +19,23 @@ HIPCC_FLAGS = [
 ]
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every source with hipcc (cross-compiles without a GPU)."""
+def _compile(lib: str, sources, verbose: bool) -> str:
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB + f".tmp{os.getpid()}"
+    tmp = lib + f".tmp{os.getpid()}"
     cmd = [hipcc, *HIPCC_FLAGS, "-I", os.path.join(ROOT, "include"), "-o", tmp]
-    cmd += ["-x", "hip"] + [os.path.join(CSRC, s) for s in SOURCES]
+    cmd += ["-x", "hip"] + [os.path.join(CSRC, s) for s in sources]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.check_call(cmd)
-    os.replace(tmp, LIB)
-    return LIB
+    os.replace(tmp, lib)
+    return lib
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile every source with hipcc (cross-compiles without a GPU): the solver library and
+    the benchmark's roof microbenchmarks (a library of their own, not loaded by the solver)."""
+    _compile(ROOFS_LIB, ROOFS_SOURCES, verbose)
+    return _compile(LIB, SOURCES, verbose)
 
 
 if __name__ == "__main__":

@@ -22,7 +22,7 @@ namespace {
 constexpr uint32_t kInf = 1u << 30;
 constexpr int kT = 8;  // stage-block size of the fill
 constexpr int kCH = 4;  // 64-column chunks of m per gemm work-group
-constexpr int kRowWG = 256;  // threads (columns of m) per row_kernel work-group
+constexpr int kRowWG = 256;  // threads (columns of m) per work-group of the row kernels
 std::atomic<int> g_last_hip_error{0};
 
 inline bool hip_ok(hipError_t e) {
@@ -72,6 +72,11 @@ inline bool hip_ok(hipError_t e) {
 //   need  [B][L][L] int32  feasibility frontier: smallest m at which cell (i, j) can be finite
 //   kq    [B][L]   double  P[q] + (q + 1) / 256: forward sweep up to split q, candidate number
 //                          in the fraction bits
+//   prog  [B][tiles][chunks] int32  rows of tile (I, J) finished by tile_rows_kernel for the chunk
+//                          of 64 columns; tiles = nblk (nblk + 1) / 2, chunks = pitch / 64
+//   tick  [nblk][4] int32  ticket counter of the tile_rows_kernel launch of diagonal D, group g
+//   fault [1]      int32   set when a bounded wait inside tile_rows_kernel expired
+// prog, tick and fault are cleared by precompute_kernel at the start of every solve.
 struct Workspace {
     int32_t* P;
     int32_t* fb;
@@ -82,16 +87,28 @@ struct Workspace {
     int32_t* flags;
     int32_t* need;
     double* kq;
+    int32_t* prog;
+    int32_t* tick;
+    int32_t* fault;
 };
 
-inline size_t align64(size_t n) { return (n + 63) & ~size_t(63); }
+constexpr int kBand = kRowWG;  // columns of m per work-group of the row kernels
+constexpr int kTickGroups = 4;
 
-inline size_t ws_ints(int L, int B) {
+inline size_t align64(size_t n) { return (n + 63) & ~size_t(63); }
+__host__ __device__ inline int blocks_of(int L) { return (L + kT - 1) / kT; }
+__host__ __device__ inline size_t tiles_of(int L) { return size_t(blocks_of(L)) * (blocks_of(L) + 1) / 2; }
+__host__ __device__ inline int bands_of(int pitch) { return (pitch + kBand - 1) / kBand; }
+// index of tile (I, J), I <= J, in the row-major packed block triangle
+__host__ __device__ inline int tile_index(int nblk, int I, int J) { return I * nblk - (I * (I - 1)) / 2 + (J - I); }
+
+inline size_t ws_ints(int L, int pitch, int B) {
     return align64(size_t(B) * (L + 1)) + 3 * align64(size_t(B) * L) + 3 * align64(size_t(B) * L * L) +
-           align64(size_t(B)) + 2 * align64(size_t(B) * L);
+           align64(size_t(B)) + 2 * align64(size_t(B) * L) + align64(size_t(B) * tiles_of(L) * (pitch / 64)) +
+           align64(size_t(blocks_of(L)) * kTickGroups) + 64;
 }
 
-inline Workspace carve(void* base, int L, int B) {
+inline Workspace carve(void* base, int L, int pitch, int B) {
     int32_t* p = static_cast<int32_t*>(base);
     Workspace w;
     w.P = p;      p += align64(size_t(B) * (L + 1));
@@ -102,7 +119,10 @@ inline Workspace carve(void* base, int L, int B) {
     w.mnull = p;  p += align64(size_t(B) * L * L);
     w.flags = p;  p += align64(size_t(B));
     w.need = p;   p += align64(size_t(B) * L * L);
-    w.kq = reinterpret_cast<double*>(p);
+    w.kq = reinterpret_cast<double*>(p);  p += 2 * align64(size_t(B) * L);
+    w.prog = p;   p += align64(size_t(B) * tiles_of(L) * (pitch / 64));
+    w.tick = p;   p += align64(size_t(blocks_of(L)) * kTickGroups);
+    w.fault = p;
     return w;
 }
 
@@ -112,7 +132,23 @@ struct Ctx {
     Workspace ws;
     int32_t* cost;
     uint8_t* arg;
+    // measurement only (ckpt_solve_profiled), else null: kWorkSets sets of four counters, [0] bytes
+    // of table loads the gemm's waves asked for, [1] bytes they stored, [2], [3] the same for the
+    // row kernel; a wave adds to the set its position selects, the host sums the sets
+    unsigned long long* work;
 };
+constexpr int kWorkSets = 256;
+
+// One lane per wave adds the wave's byte counts (per lane 4 bytes a load, 5 a stored cell).
+template <bool CNT>
+__device__ __forceinline__ void count_work(unsigned long long* work, int slot, unsigned loads, unsigned cells) {
+    if constexpr (!CNT) return;  // the counting variants are separate instantiations: no cost otherwise
+    if (work && (threadIdx.x & 63) == 0) {
+        const unsigned set = (blockIdx.x * 7u + blockIdx.y * 13u + blockIdx.z * 29u + (threadIdx.x >> 6)) % kWorkSets;
+        atomicAdd(work + set * 4 + slot, 256ull * loads);
+        atomicAdd(work + set * 4 + slot + 1, 320ull * cells);
+    }
+}
 
 __host__ __device__ inline int tri_row(int L, int i, int j) {  // 0-based i <= j
     return i * L - (i * (i - 1)) / 2 + (j - i);
@@ -133,6 +169,14 @@ __global__ void __launch_bounds__(256) precompute_kernel(ckpt_chains_t ch, int L
     __shared__ int s_flags;
     __shared__ int32_t s_uf[CKPT_MAX_L + 2];
     if (tid == 0) s_flags = 0;
+    {   // progress flags of this chain's tiles, and (first block) the ticket counters and the fault word
+        const size_t n = tiles_of(L) * (pitch / 64);
+        for (size_t k = tid; k < n; k += blockDim.x) ws.prog[size_t(b) * n + k] = 0;
+        if (b == 0) {
+            for (int k = tid; k < blocks_of(L) * kTickGroups; k += blockDim.x) ws.tick[k] = 0;
+            if (tid == 0) ws.fault[0] = 0;
+        }
+    }
     __syncthreads();
 
     // Sizes are clamped into [0, 2^28] so that thresholds of a bad chain cannot overflow.
@@ -354,12 +398,12 @@ __device__ __forceinline__ void finish_row(const Ctx& c, size_t chain, const int
 // (all values are integers below 2^34 scaled by 2^-8, exact in float64).
 // Splits whose operands are infeasible for the whole chunk (frontier test) are dropped
 // from the work list before the pipeline starts.
-// Output, rows 0..6 of the tile: cost[] <- unsaturated partial minimum (0xffffffff if none),
-// arg[] <- its number; row_kernel finishes them.  Row 7 has no split in its own row block, so
+// Output, rows 0..6 of the tile: cost[] <- partial minimum clamped to 2^31 - 1, with bit 31 set as
+// the mark "not finished", arg[] <- its number; the row kernels finish them.  Row 7 has no split in its own row block, so
 // its partial minimum stays in registers and the wave finishes the row itself.
 // KS > 1 (launches with too few tiles to fill the chip): KS waves share one chunk, each takes
 // every KS-th entry of the work list, and their key tiles are merged through LDS at the end.
-template <int NB, int UNR, int CH, int KS>
+template <int NB, int UNR, int CH, int KS, bool CNT>
 __global__ void __launch_bounds__(64 * CH * KS, 2) gemm_kernel(Ctx c, int D) {
     constexpr int T = kT;
     static_assert(T == 8, "one wave per 8x8 tile");
@@ -485,6 +529,7 @@ __global__ void __launch_bounds__(64 * CH * KS, 2) gemm_kernel(Ctx c, int D) {
         const int bulk = n / STEPS, tail = (n - bulk * STEPS + NB - 1) / NB;
         for (int it = 0; it < bulk; ++it) steps(std::integral_constant<int, STEPS>{}, k);
         for (int it = 0; it < tail; ++it) steps(std::integral_constant<int, NB>{}, k);
+        count_work<CNT>(c.work, 0, 16u * unsigned(NB - 1 + bulk * STEPS + tail * NB), 0);
     }
 
     if constexpr (KS > 1) {
@@ -528,6 +573,10 @@ __global__ void __launch_bounds__(64 * CH * KS, 2) gemm_kernel(Ctx c, int D) {
         cst = k < 0x1p32 ? uint32_t(fl) - Pi : 0xffffffffu;
         num = uint32_t((fmin(k, 0x1p33) - fl) * 256.0);
     };
+    // A partial minimum is stored with bit 31 set: a finished cell never exceeds 2^30, so whoever
+    // reads the table can tell a cell that still waits for its row kernel from a finished one.
+    // Partial minima of 2^31 - 1 and more are infeasible whatever they were and are clamped.
+    auto tagged = [](uint32_t cst) { return min(cst, 0x7fffffffu) | 0x80000000u; };
 #pragma unroll
     for (int r = 0; r < 7; ++r) {
         const uint32_t Pi = P[i0 + r];
@@ -537,11 +586,12 @@ __global__ void __launch_bounds__(64 * CH * KS, 2) gemm_kernel(Ctx c, int D) {
             if (cc < cend) {
                 uint32_t cst, num;
                 partial(r, cc, Pi, cst, num);
-                c.cost[row + size_t(cc) * pitch] = int32_t(cst);
+                c.cost[row + size_t(cc) * pitch] = int32_t(tagged(cst));
                 c.arg[row + size_t(cc) * pitch] = uint8_t(num);
             }
         }
     }
+    count_work<CNT>(c.work, 0, live7 ? 36u : 0u, 8u * unsigned(cend));
     if (live7) {
         uint32_t best[8], pick[8];
 #pragma unroll
@@ -638,7 +688,7 @@ __global__ void __launch_bounds__(kRowWG) row_kernel(Ctx c, int D) {
 #pragma unroll
         for (int cc = 0; cc < T; ++cc) {
             const size_t o = chain + size_t(rowi + jc[cc]) * pitch + m;
-            pc[cc] = uint32_t(c.cost[o]);
+            pc[cc] = uint32_t(c.cost[o]) & 0x7fffffffu;  // bit 31 marks the gemm's partial minima
             pp[cc] = c.arg[o];
         }
     }
@@ -665,6 +715,405 @@ __global__ void __launch_bounds__(kRowWG) row_kernel(Ctx c, int D) {
             if (pc[cc] < best[cc]) best[cc] = pc[cc], pick[cc] = pp[cc];
     }
     finish_row<T, CF, DC>(c, chain, P, mall, mnull, L, pitch, i, jb, cend, jc, fbi, m, best, pick, tj, al);
+}
+
+// ---------------------------------------------------------------------------
+// All rows of every tile of one block diagonal in ONE launch.
+//
+// A work-group owns one band of kBand columns of m of one tile and finishes its rows bottom-up.
+// Row r needs the row below it in the same tile at m - shift: from its own band, and from lower
+// bands that other work-groups finish in the same launch.
+//   - Inside the band the row below travels through LDS (two buffers, one barrier per row).
+//   - Between bands it travels through memory.  Work-groups take their work by ticket (an atomic
+//     counter), bands in ascending order, so whatever a wave waits for belongs to a work-group
+//     that already runs -- no deadlock, whatever order the hardware starts work-groups in.
+//     D >= 2: before its row is finished a cell holds the gemm's partial minimum, marked by bit 31
+//     (finished cells never exceed 2^30), so a reader needs no flag and a writer never waits for
+//     its stores: a lane that finds the mark simply reads again.  D < 2: the cells hold whatever
+//     the caller's buffer held, so every wave publishes "rows finished" for its chunk of 64
+//     columns once its stores of the row have completed, and readers wait for those flags
+//     (looked at one row ahead of the need, while the wave waits for its own stores).
+//     Every wait is bounded: when it expires the kernel sets the fault word and all work-groups
+//     drain (ckpt_check_inputs then reports CKPT_E_INTERNAL).
+// Coherence between compute units and between the L2 caches of the eight dies, without cache
+// flushes: a cell of the table is written once per solve and only read after it was published.
+// Finished rows are stored with device-scope stores (written through to memory before the
+// store counts as complete) and rows of the same launch are read with device-scope loads
+// (never served from a compute unit's L1 or from a stale line of another die's L2).  Lanes whose
+// shifted column would be negative read nothing (an out-of-range buffer offset returns 0), so
+// no line of the table is touched before its owner has written it.
+// Each loaded operand of a split is kept in registers for all rows that use it: per tile and
+// lane 7 x 8 + 28 + 64 operand loads instead of the 252 + 224 + 64 of one launch per row.
+// ---------------------------------------------------------------------------
+constexpr uint32_t kNoRead = 0xfffffff0u;  // buffer offset beyond any table: the load returns 0, no access
+constexpr int kSpinLimit = 1 << 20;        // polls of a wait before it gives up (seconds, never reached)
+
+__device__ __forceinline__ uint32_t ld32_dev(rsrc_t tab, uint32_t elem, uint32_t off) {  // device-scope load
+    return uint32_t(__builtin_amdgcn_raw_buffer_load_b32(tab, int(off), int(elem << 2), 16));
+}
+
+// Per-tile parameters of the row kernel, fetched once into LDS by the whole work-group: the
+// rows' thresholds and frontier, prefix sums, shifts.  Inside the row steps nothing but table
+// cells comes from memory, so a step costs one memory round trip.
+struct TilePar {
+    int32_t mall[kT][kT], mnull[kT][kT], need[kT][kT];  // [r][cc]: cell (i0 + r, j_cc)
+    int32_t Pi[kT + 1];   // P[i0 + u], u = 0..8
+    int32_t Pj[kT];       // P[min(jb + c2 + 1, L - 1)]
+    int32_t wsh[kT + 1];  // shift of split q = i0 + u
+    int32_t wabs[kT], fb[kT];
+};
+
+template <int DC>
+struct TileCtx {
+    Ctx c;
+    const TilePar* par;
+    int b, I, J, L, pitch, i0, jb, cend, band;
+    size_t chain;
+    rsrc_t tab;
+    const int32_t* P;
+    const int32_t* wsh;
+    uint32_t m, moff;
+    int jc[kT];
+    int32_t* prog;    // progress of this tile: [chunks of 64 columns]
+    int chunk0;       // first chunk of this band
+    int nwait;        // chunks below the band that this wave's shifted reads can reach
+    int seen;         // lane k < nwait: progress of chunk chunk0 - 1 - k as last looked at
+    bool dead;        // a wait expired: stop working, keep meeting the barriers (per wave)
+    bool idle;        // this wave's columns lie past the end of the rows (wave-uniform)
+    // right operands kept for all rows: ri[u][cc] = cell (i0 + u, j_cc) at m - omega_a^{i0+u}, u = 1..8
+    // (rows of this tile; u = 8 is the first stage of the column block, D = 1 only);
+    // rj[c2][cc] = cell (jb + c2 + 1, j_cc) at its shift, c2 < cc (column block, D >= 1)
+    uint32_t ri[kT + 1][kT];
+    uint32_t rj[kT][kT];
+};
+
+// Requests the progress of the chunks below the band (lane k looks at chunk chunk0 - 1 - k);
+// consumed by the next wait_rows_below, by which time the load has long returned.
+template <int DC>
+__device__ __forceinline__ void look_below(TileCtx<DC>& x) {
+    const int k = threadIdx.x & 63;
+    if (k < x.nwait) x.seen = __hip_atomic_load(x.prog + x.chunk0 - 1 - k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Every wave for itself: until each of the nwait chunks below the band has finished `rows` rows.
+template <int DC>
+__device__ __forceinline__ void wait_rows_below(TileCtx<DC>& x, int rows) {
+    if (x.nwait == 0 || x.dead) return;
+    const int lane = threadIdx.x & 63;
+    bool ok = __all(lane >= x.nwait || x.seen >= rows) && x.nwait <= 64;
+    for (int spin = 0; !ok && spin < kSpinLimit; ++spin) {
+        ok = true;
+        for (int k = lane; k < x.nwait; k += 64)
+            ok = ok && __hip_atomic_load(x.prog + x.chunk0 - 1 - k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= rows;
+        ok = __all(ok);
+        if (ok) break;
+        if ((spin & 63) == 63 && __hip_atomic_load(x.c.ws.fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)
+            break;
+        __builtin_amdgcn_s_sleep(2);
+    }
+    if (!ok) {
+        x.dead = true;
+        if (lane == 0) __hip_atomic_store(x.c.ws.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+// Cell (q, jb + cc) of a row finished in THIS launch, at column m - sh: from LDS if that column
+// lies in this band (`below` = the row's buffer), else from the table with a device-scope load.
+// D >= 2: the cells of the tile hold the gemm's partial minima, marked by bit 31, until their
+// row is finished, so the read needs no flag: a lane that finds the mark reads again (bounded).
+// D < 2: the caller has waited for the progress flags of the chunks that are read.
+template <int DC>
+__device__ __forceinline__ void read_row_below(TileCtx<DC>& x, const uint32_t (*below)[kBand], int q, uint32_t sh,
+                                               int first_cc, uint32_t (&out)[kT]) {
+    const int t = int(threadIdx.x) - int(sh);  // column inside the band
+    const bool in_band = t >= 0;
+    const uint32_t off = (!in_band && x.m >= sh) ? x.moff : kNoRead;
+    const uint32_t rq = uint32_t(row_base(x.L, q));
+    uint32_t mem[kT];
+    auto fetch = [&]() {
+        uint32_t marks = 0;
+#pragma unroll
+        for (int cc = 0; cc < kT; ++cc) {
+            mem[cc] = 0;
+            if (cc >= first_cc && cc < x.cend)  // only cells that exist are read
+                mem[cc] = ld32_dev(x.tab, (rq + uint32_t(x.jb + cc)) * uint32_t(x.pitch) - sh, off);
+            marks |= mem[cc];
+        }
+        return (marks >> 31) != 0;
+    };
+    bool again = fetch();
+    if (DC == 2) {
+        int spin = 0;
+        while (__any(again)) {  // some lane met a cell that its owner has not finished yet
+            if (++spin > kSpinLimit ||
+                ((spin & 63) == 0 && __hip_atomic_load(x.c.ws.fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
+                x.dead = true;
+                if ((threadIdx.x & 63) == 0)
+                    __hip_atomic_store(x.c.ws.fault, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                break;
+            }
+            __builtin_amdgcn_s_sleep(2);
+            if (again) again = fetch();
+        }
+    }
+#pragma unroll
+    for (int cc = 0; cc < kT; ++cc) {
+        if (cc >= first_cc && cc < x.cend) {
+            const uint32_t lds = below[cc][in_band ? t : 0];
+            out[cc] = in_band ? lds : mem[cc];
+        }
+    }
+}
+
+template <int DC, int R, bool CNT>
+__device__ __forceinline__ void tile_row(TileCtx<DC>& x, uint32_t (*s_row)[kT][kBand]) {
+    constexpr int T = kT;
+    constexpr int RF = (DC == 2) ? T - 2 : T - 1;                      // first row this kernel finishes
+    constexpr int CF = (DC == 0) ? R : 0;                              // first column with j >= i
+    constexpr int NQ = (DC == 0) ? 0 : (DC == 1 ? T - R : T - 1 - R);  // splits in the row block (D = 1: and q = jb)
+    constexpr int NQA = NQ > 0 ? NQ : 1;
+    constexpr int U = R + 1;                                           // the row below
+    const int L = x.L, pitch = x.pitch;
+    const int i = x.i0 + R;
+    if (i >= L) return;  // ragged last block: uniform over the work-group
+    const bool below_here = R < RF && i + 1 < L;  // the row below exists and belongs to this launch
+    const uint32_t m = x.m, moff = x.moff;
+    const TilePar& par = *x.par;
+    const int rowi = tri_row(L, i, i) - i;  // + j = row of (i, j)
+    const uint32_t (*below)[kBand] = s_row[U & 1];
+    uint32_t (*mine)[kBand] = s_row[R & 1];
+    uint32_t val[T];
+#pragma unroll
+    for (int cc = 0; cc < T; ++cc) val[cc] = kInf;
+
+    if (DC < 2 && below_here) wait_rows_below(x, RF - R);
+    if (!x.dead && !x.idle) {
+        // ---- loads of this row, all issued together ----
+        // the operands that the row below contributes to all rows above it, kept
+        if ((U < T || DC == 1) && x.i0 + U < L) {
+            const int q = x.i0 + U;
+            const uint32_t sh = uint32_t(par.wsh[U]);
+            if (below_here) {
+                read_row_below(x, below, q, sh, DC == 0 ? U : 0, x.ri[U]);
+            } else {  // finished by an earlier launch
+                const uint32_t off = m >= sh ? moff : kNoRead;
+#pragma unroll
+                for (int cc = (DC == 0 ? U : 0); cc < T; ++cc)
+                    if (cc < x.cend)
+                        x.ri[U][cc] = ld32(x.tab, uint32_t(row_base(L, q) + x.jb + cc) * uint32_t(pitch) - sh, off);
+            }
+        }
+        int row_need = 1 << 30;
+#pragma unroll
+        for (int cc = CF; cc < T; ++cc)
+            row_need = min(row_need, DC == 2 ? par.need[R][cc] : min(par.mall[R][cc], par.mnull[R][cc]));
+        const int m_hi = __builtin_amdgcn_readfirstlane(int(m)) | 63;
+        const bool live = m_hi >= row_need;  // else the whole chunk lies below the feasibility frontier of the row
+        const unsigned cols = unsigned(max(0, x.cend - CF));  // cells of the row that exist
+        count_work<CNT>(x.c.work, 2, cols + (live ? unsigned(NQ) + (DC == 2 ? 10u : 0u) + cols : 0u), cols);
+        const uint32_t Pi = par.Pi[R];
+        const uint32_t fbi = par.fb[R];
+        const uint32_t wabi = par.wabs[R];
+        uint32_t nl[NQA], pc[T], pp[T], al[T];
+#pragma unroll
+        for (int cc = 0; cc < T; ++cc) al[cc] = 0, pc[cc] = 0xffffffffu, pp[cc] = 0;
+        if (live) {
+#pragma unroll
+            for (int u = 0; u < NQ; ++u) nl[u] = ld32(x.tab, uint32_t(rowi + i + u) * uint32_t(pitch), moff);
+            if (DC == 2) {  // gemm partial
+#pragma unroll
+                for (int cc = 0; cc < T; ++cc) {
+                    const size_t o = x.chain + size_t(rowi + x.jc[cc]) * pitch + m;
+                    pc[cc] = uint32_t(x.c.cost[o]) & 0x7fffffffu;  // bit 31 marks the gemm's partial minima
+                    pp[cc] = x.c.arg[o];
+                }
+            }
+            // C_all: cell (i + 1, j) at m - omega_abar^{i+1}, for j > i
+            if (below_here) {
+                read_row_below(x, below, i + 1, wabi, DC == 0 ? CF + 1 : CF, al);
+            } else if (i + 1 < L) {  // row 0 of the tile below, or row 7 finished by the gemm: earlier launches
+                const uint32_t off = m >= wabi ? moff : kNoRead;
+#pragma unroll
+                for (int cc = (DC == 0 ? CF + 1 : CF); cc < T; ++cc)
+                    if (cc < x.cend)
+                        al[cc] = ld32(x.tab, uint32_t(row_base(L, i + 1) + x.jb + cc) * uint32_t(pitch) - wabi, off);
+            }
+        }
+        if (live) {
+            // ---- evaluation, in candidate-number order with strict '<' ----
+            uint32_t best[T], pick[T];
+#pragma unroll
+            for (int cc = 0; cc < T; ++cc) best[cc] = 0xffffffffu, pick[cc] = 0;
+#pragma unroll
+            for (int u = 0; u < NQ; ++u) {
+                const int q = i + 1 + u;
+                const uint32_t lb = nl[u] + (uint32_t(par.Pi[R + 1 + u]) - Pi);
+#pragma unroll
+                for (int cc = 0; cc < T; ++cc) {
+                    const uint32_t v = lb + x.ri[R + 1 + u][cc];
+                    if (v < best[cc]) best[cc] = v, pick[cc] = q + 1;
+                }
+            }
+            if (DC == 2) {
+#pragma unroll
+                for (int cc = 0; cc < T; ++cc)
+                    if (pc[cc] < best[cc]) best[cc] = pc[cc], pick[cc] = pp[cc];
+            }
+#pragma unroll
+            for (int cc = CF; cc < T; ++cc) {
+#pragma unroll
+                for (int c2 = CF; c2 < cc; ++c2) {  // splits in the column block: left operand (i, q-1) = val[c2]
+                    const int q = min(x.jb + c2 + 1, L - 1);
+                    const uint32_t r = (DC == 0) ? x.ri[c2 + 1][cc] : x.rj[c2][cc];
+                    const uint32_t v = val[c2] + (uint32_t(par.Pj[c2]) - Pi) + r;
+                    if (v < best[cc]) best[cc] = v, pick[cc] = q + 1;
+                }
+                const uint32_t ck = (m >= uint32_t(par.mnull[R][cc])) ? min(best[cc], kInf) : kInf;
+                uint32_t all = fbi;
+                if (DC != 0 || cc > CF) all += al[cc];  // j > i
+                all = (m >= uint32_t(par.mall[R][cc])) ? min(all, kInf) : kInf;
+                const bool take_all = all < kInf && all <= ck;
+                val[cc] = take_all ? all : ck;
+                pick[cc] = take_all ? uint32_t(i + 1) : (ck < kInf ? pick[cc] : 0u);
+            }
+#pragma unroll
+            for (int cc = CF; cc < T; ++cc) {
+                if (cc < x.cend) {
+                    const size_t o = x.chain + size_t(rowi + x.jc[cc]) * pitch + m;
+                    __hip_atomic_store(x.c.cost + o, int32_t(val[cc]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    x.c.arg[o] = uint8_t(pick[cc]);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int cc = CF; cc < T; ++cc) {
+                if (cc < x.cend) {
+                    const size_t o = x.chain + size_t(rowi + x.jc[cc]) * pitch + m;
+                    __hip_atomic_store(x.c.cost + o, int32_t(kInf), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    x.c.arg[o] = 0;
+                }
+            }
+        }
+        if (R > 0) {
+            // the rows above read this row from LDS (this band) or from memory (bands above)
+#pragma unroll
+            for (int cc = CF; cc < T; ++cc) mine[cc][threadIdx.x] = val[cc];
+            if (DC < 2) {
+                // The cells of these tiles hold whatever the caller's buffer held: readers in other
+                // bands need a flag.  Publish the row for this wave's chunk as soon as its stores
+                // have completed; the look at the chunks below returns together with them.
+                look_below(x);
+                __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                __builtin_amdgcn_s_waitcnt(0);
+                if ((threadIdx.x & 63) == 0)
+                    __hip_atomic_store(x.prog + (x.m >> 6), RF - R + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+    }
+    if (R > 0) __syncthreads();  // the row is in LDS for the waves of this band
+}
+
+template <int DC, int R, bool CNT>
+struct TileRows {
+    static __device__ __forceinline__ void run(TileCtx<DC>& x, uint32_t (*s_row)[kT][kBand]) {
+        tile_row<DC, R, CNT>(x, s_row);
+        if constexpr (R > 0) TileRows<DC, R - 1, CNT>::run(x, s_row);
+    }
+};
+
+template <int DC, bool CNT>
+__global__ void __launch_bounds__(kRowWG, 3) tile_rows_kernel(Ctx c, int D, int32_t* tick) {
+    constexpr int T = kT;
+    constexpr int RF = (DC == 2) ? T - 2 : T - 1;
+    __shared__ int s_ticket, s_fault;
+    __shared__ uint32_t s_row[2][kT][kBand];  // the last two finished rows of this band
+    __shared__ TilePar s_par;
+    if (threadIdx.x == 0) {
+        s_ticket = atomicAdd(tick, 1);
+        s_fault = __hip_atomic_load(c.ws.fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    const uint32_t ntile = gridDim.y, per_band = gridDim.y * gridDim.z;
+    const uint32_t ticket = uint32_t(s_ticket);
+    if (ticket >= gridDim.x * per_band) return;  // cannot happen: one ticket per work-group
+    TileCtx<DC> x;
+    x.c = c;
+    x.band = int(ticket / per_band);  // bands in ascending order
+    const uint32_t rest = ticket - uint32_t(x.band) * per_band;
+    x.I = int(rest % ntile);
+    x.J = x.I + D;
+    x.b = c.b0 + int(rest / ntile);
+    x.L = c.L;
+    x.pitch = c.pitch;
+    x.i0 = x.I * T;
+    x.jb = x.J * T;
+    x.cend = min(T, c.L - x.jb);
+    x.chain = size_t(x.b) * c.rows * c.pitch;
+    x.tab = table_rsrc(c.cost + x.chain, uint32_t(c.rows) * uint32_t(c.pitch) * 4u);
+    x.P = c.ws.P + size_t(x.b) * (c.L + 1);
+    x.wsh = c.ws.wsh + size_t(x.b) * c.L;
+    x.m = uint32_t(x.band) * kBand + threadIdx.x;
+    x.moff = x.m * 4;
+    x.seen = 0;
+    x.dead = s_fault != 0;  // an earlier work-group gave up: drain
+#pragma unroll
+    for (int cc = 0; cc < T; ++cc) x.jc[cc] = min(x.jb + cc, c.L - 1);
+#pragma unroll
+    for (int u = 0; u <= T; ++u)
+#pragma unroll
+        for (int cc = 0; cc < T; ++cc) x.ri[u][cc] = 0;
+#pragma unroll
+    for (int c2 = 0; c2 < T; ++c2)
+#pragma unroll
+        for (int cc = 0; cc < T; ++cc) x.rj[c2][cc] = 0;
+    {   // parameters of the tile: one fetch by the whole work-group
+        const int t = threadIdx.x, L = c.L;
+        const size_t bL = size_t(x.b) * L;
+        if (t < 64) {
+            const int r = t >> 3, i = min(x.i0 + r, L - 1);
+            const size_t at = (bL + i) * L + min(x.jb + (t & 7), L - 1);  // no dynamic index into x: it stays in registers
+            s_par.mall[r][t & 7] = c.ws.mall[at];
+            s_par.mnull[r][t & 7] = c.ws.mnull[at];
+            s_par.need[r][t & 7] = DC == 2 ? c.ws.need[at] : 0;  // D < 2 runs beside the frontier kernel
+        } else if (t < 64 + T + 1) {
+            const int u = t - 64, q = min(x.i0 + u, L - 1);
+            s_par.Pi[u] = x.P[min(x.i0 + u, L)];
+            s_par.wsh[u] = x.wsh[q];
+        } else if (t >= 96 && t < 96 + T) {
+            const int r = t - 96, q = min(x.jb + r + 1, L - 1), i = min(x.i0 + r, L - 1);
+            s_par.Pj[r] = x.P[q];
+            s_par.wabs[r] = c.ws.wabs[bL + i];
+            s_par.fb[r] = c.ws.fb[bL + i];
+        }
+    }
+    x.par = &s_par;
+    __syncthreads();
+    const int nblk = blocks_of(c.L);
+    x.prog = c.ws.prog + (size_t(x.b) * tiles_of(c.L) + tile_index(nblk, x.I, x.J)) * (c.pitch / 64);
+    x.chunk0 = x.band * (kBand / 64);
+    {   // chunks below the band that the shifts of this tile's rows can reach from this wave's columns
+        int reach = 0;
+        for (int r = 0; r < T; ++r) reach = max(reach, max(s_par.wsh[r], s_par.wabs[r]));
+        const int m0 = __builtin_amdgcn_readfirstlane(int(x.m));  // first column of the wave
+        x.nwait = max(0, x.chunk0 - (max(0, m0 - reach) >> 6));
+    }
+    // The band may lie past the end of the rows (pitch is a multiple of 64, not of kBand): those
+    // waves read and store nothing but still meet every barrier.
+    x.idle = x.m >= uint32_t(c.pitch);
+    if (DC >= 1 && !x.dead && !x.idle) {
+        // operands of the splits in the column block, finished by earlier launches
+#pragma unroll
+        for (int cc = 1; cc < T; ++cc)
+#pragma unroll
+            for (int c2 = 0; c2 < cc; ++c2) {
+                const int q = min(x.jb + c2 + 1, c.L - 1);
+                const uint32_t sh = uint32_t(x.wsh[q]);
+                x.rj[c2][cc] = ld32(x.tab, uint32_t(row_base(c.L, q) + x.jc[cc]) * uint32_t(c.pitch) - sh,
+                                    x.m >= sh ? x.moff : kNoRead);
+            }
+        count_work<CNT>(c.work, 2, 28u, 0);
+    }
+    TileRows<DC, RF, CNT>::run(x, s_row);
 }
 
 using RowFn = void (*)(Ctx, int);
@@ -936,7 +1385,10 @@ struct Profile {
     hipStream_t stream = nullptr;
     std::vector<hipEvent_t> events;
     std::vector<int> kinds;
+    unsigned long long* work = nullptr;  // device, 4 counters
+    bool trail = true;                   // record an event after every launch
     bool mark(int kind) {
+        if (!trail) return true;
         hipEvent_t e;
         if (!hip_ok(hipEventCreate(&e))) return false;
         events.push_back(e);
@@ -963,6 +1415,7 @@ struct Device {
     hipStream_t stream[kSideStreams] = {};
     hipEvent_t join[kSideStreams] = {};
     hipEvent_t fork = nullptr;
+    hipEvent_t stagger = nullptr;
     bool helpers_tried = false, helpers_ok = false;
     void* scratch = nullptr;
     std::mutex busy;  // one fork/join sequence at a time per device
@@ -987,7 +1440,8 @@ bool ensure_helpers(Device& d) {
     std::lock_guard<std::mutex> guard(g_devices_lock);
     if (!d.helpers_tried) {
         d.helpers_tried = true;
-        bool ok = hip_ok(hipEventCreateWithFlags(&d.fork, hipEventDisableTiming));
+        bool ok = hip_ok(hipEventCreateWithFlags(&d.fork, hipEventDisableTiming)) &&
+                  hip_ok(hipEventCreateWithFlags(&d.stagger, hipEventDisableTiming));
         for (int k = 0; k < kSideStreams && ok; ++k)
             ok = hip_ok(hipStreamCreateWithFlags(&d.stream[k], hipStreamNonBlocking)) &&
                  hip_ok(hipEventCreateWithFlags(&d.join[k], hipEventDisableTiming));
@@ -1034,6 +1488,11 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
          reinterpret_cast<uintptr_t>(workspace)) & 255)
         return CKPT_E_ARG;
     const int want_groups = opts ? opts->groups : 0, want_ks = opts ? opts->list_split : 0;
+    const int row_mode = opts ? opts->row_launches : 0;
+    if (row_mode != 0 && row_mode != 1) return CKPT_E_ARG;
+    const bool fused_rows = row_mode == 0;
+    const int stagger = opts ? opts->stagger : 0;
+    unsigned long long* work = prof ? prof->work : nullptr;
     if (want_groups < 0 || want_groups > kSideStreams + 1) return CKPT_E_ARG;
     if (want_ks != 0 && want_ks != 1 && want_ks != 2 && want_ks != 4) return CKPT_E_ARG;
     bool own_side = false;
@@ -1045,7 +1504,7 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int pitch = int(ckpt_row_pitch(M));
     const int rows = int(ckpt_table_rows(L));
-    const Workspace ws = carve(workspace, L, B);
+    const Workspace ws = carve(workspace, L, pitch, B);
 
     const size_t frontier_lds = ckpt_table_rows(L) * sizeof(int32_t);
     if (frontier_lds > 48 * 1024 && !allow_frontier_lds()) return CKPT_E_HIP;
@@ -1109,8 +1568,18 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
         hipLaunchKernelGGL(frontier_kernel, dim3(B), dim3(1024), frontier_lds, gs[1], *chains, L, ws);
         CKPT_AFTER_LAUNCH(CKPT_K_FRONTIER);
 
+        const int nbands = bands_of(pitch);
         for (int D = 0; D < 2 && D < nblk; ++D) {
-            const Ctx ctx{L, M, pitch, rows, 0, ws, cost, arg};
+            const Ctx ctx{L, M, pitch, rows, 0, ws, cost, arg, work};
+            if (fused_rows) {
+                const dim3 grid(nbands, nblk - D, B);
+                int32_t* tick = ws.tick + D * kTickGroups;
+                const auto fn = D == 0 ? (work ? tile_rows_kernel<0, true> : tile_rows_kernel<0, false>)
+                                       : (work ? tile_rows_kernel<1, true> : tile_rows_kernel<1, false>);
+                hipLaunchKernelGGL(fn, grid, dim3(kRowWG), 0, st, ctx, D, tick);
+                CKPT_AFTER_LAUNCH(CKPT_K_ROW);
+                continue;
+            }
             const auto& rowfn = D == 0 ? kRow0 : kRow1;
             for (int r = T - 1; r >= 0; --r) {
                 hipLaunchKernelGGL(rowfn[r], dim3(gx_row, nblk - D, B), dim3(kRowWG), 0, st, ctx, D);
@@ -1132,21 +1601,36 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
             const int ks = want_ks ? want_ks : (waves <= 600 ? 4 : (waves <= 1700 ? 2 : 1));
             const int gx = (pitch / 64 + kCH / ks - 1) / (kCH / ks);
             for (int g = 0; g < groups; ++g) {
-                const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
+                const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg, work};
                 const dim3 grid(gx, nblk - D, first[g + 1] - first[g]), block(64 * kCH);
-                if (ks == 4)
-                    hipLaunchKernelGGL((gemm_kernel<3, 3, kCH / 4, 4>), grid, block, 0, gs[g], ctx, D);
-                else if (ks == 2)
-                    hipLaunchKernelGGL((gemm_kernel<3, 3, kCH / 2, 2>), grid, block, 0, gs[g], ctx, D);
-                else
-                    hipLaunchKernelGGL((gemm_kernel<3, 3, kCH, 1>), grid, block, 0, gs[g], ctx, D);
+                const auto fn = ks == 4 ? (work ? gemm_kernel<3, 3, kCH / 4, 4, true> : gemm_kernel<3, 3, kCH / 4, 4, false>)
+                              : ks == 2 ? (work ? gemm_kernel<3, 3, kCH / 2, 2, true> : gemm_kernel<3, 3, kCH / 2, 2, false>)
+                                        : (work ? gemm_kernel<3, 3, kCH, 1, true> : gemm_kernel<3, 3, kCH, 1, false>);
+                hipLaunchKernelGGL(fn, grid, block, 0, gs[g], ctx, D);
                 CKPT_AFTER_LAUNCH(CKPT_K_GEMM);
+                if (D == 2 && g == 0 && side && stagger && groups >= 3) {
+                    // the second half of the groups starts when the first group's block product is
+                    // done: from then on their bandwidth-bound and latency-bound phases alternate
+                    if (!hip_ok(hipEventRecord(side->stagger, gs[0]))) return CKPT_E_HIP;
+                    for (int h = (groups + 1) / 2; h < groups; ++h)
+                        if (!hip_ok(hipStreamWaitEvent(gs[h], side->stagger, 0))) return CKPT_E_HIP;
+                }
+            }
+            if (fused_rows) {  // rows 6..0 of every tile of the diagonal in one launch per group
+                for (int g = 0; g < groups; ++g) {
+                    const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg, work};
+                    const auto fn = work ? tile_rows_kernel<2, true> : tile_rows_kernel<2, false>;
+                    hipLaunchKernelGGL(fn, dim3(nbands, nblk - D, first[g + 1] - first[g]), dim3(kRowWG), 0, gs[g], ctx,
+                                       D, ws.tick + D * kTickGroups + g);
+                    CKPT_AFTER_LAUNCH(CKPT_K_ROW);
+                }
+                continue;
             }
             // rows of the groups are issued in turn so that every queue stays fed; row 7 was
             // finished by the gemm
             for (int r = T - 2; r >= 0; --r) {
                 for (int g = 0; g < groups; ++g) {
-                    const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg};
+                    const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg, work};
                     hipLaunchKernelGGL(kRow2[r], dim3(gx_row, nblk - D, first[g + 1] - first[g]), dim3(kRowWG), 0,
                                        gs[g], ctx, D);
                     CKPT_AFTER_LAUNCH(CKPT_K_ROW);
@@ -1169,7 +1653,7 @@ extern "C" {
 
 size_t ckpt_workspace_bytes(int L, int M, int B) {
     if (L < 1 || M < 0 || B < 1) return 0;
-    return ws_ints(L, B) * sizeof(int32_t);
+    return ws_ints(L, int(ckpt_row_pitch(M)), B) * sizeof(int32_t);
 }
 
 int ckpt_init(int device) {
@@ -1208,7 +1692,7 @@ int ckpt_solve_batched_opts(const ckpt_chains_t* chains, int L, int M, int B, vo
 }
 
 int ckpt_solve_profiled(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
-                        uint8_t* arg, void* workspace, float* kind_ms, int* kind_launches) {
+                        uint8_t* arg, void* workspace, float* kind_ms, int* kind_launches, double* kind_bytes) {
     if (!kind_ms || !kind_launches) return CKPT_E_ARG;
     hipStream_t st = static_cast<hipStream_t>(stream);
     Profile prof;
@@ -1225,6 +1709,28 @@ int ckpt_solve_profiled(const ckpt_chains_t* chains, int L, int M, int B, void* 
         kind_launches[prof.kinds[i]] += 1;
     }
     for (hipEvent_t e : prof.events) (void)hipEventDestroy(e);
+    if (kind_bytes && rc == CKPT_OK) {
+        // a second, untimed pass in which every wave adds up the bytes it asks for
+        for (int k = 0; k < 2 * CKPT_N_KERNEL_KINDS; ++k) kind_bytes[k] = 0.0;
+        Profile count;
+        count.stream = st;
+        count.trail = false;
+        std::vector<unsigned long long> host(size_t(kWorkSets) * 4, 0);
+        const size_t bytes = host.size() * sizeof(unsigned long long);
+        if (!hip_ok(hipMalloc(reinterpret_cast<void**>(&count.work), bytes))) return CKPT_E_HIP;
+        if (!hip_ok(hipMemsetAsync(count.work, 0, bytes, st))) rc = CKPT_E_HIP;
+        if (rc == CKPT_OK) rc = solve_impl(chains, L, M, B, stream, cost, arg, workspace, &count, nullptr, false);
+        if (rc == CKPT_OK && !hip_ok(hipMemcpyAsync(host.data(), count.work, bytes, hipMemcpyDeviceToHost, st)))
+            rc = CKPT_E_HIP;
+        if (!hip_ok(hipStreamSynchronize(st)) && rc == CKPT_OK) rc = CKPT_E_HIP;
+        (void)hipFree(count.work);
+        for (int set = 0; set < kWorkSets; ++set) {
+            kind_bytes[2 * CKPT_K_GEMM] += double(host[set * 4]);
+            kind_bytes[2 * CKPT_K_GEMM + 1] += double(host[set * 4 + 1]);
+            kind_bytes[2 * CKPT_K_ROW] += double(host[set * 4 + 2]);
+            kind_bytes[2 * CKPT_K_ROW + 1] += double(host[set * 4 + 3]);
+        }
+    }
     return rc;
 }
 
@@ -1233,7 +1739,7 @@ const char* ckpt_kernel_name(int kind) {
         case CKPT_K_PRECOMPUTE: return "precompute_kernel";
         case CKPT_K_FRONTIER: return "frontier_kernel";
         case CKPT_K_GEMM: return "gemm_kernel";
-        case CKPT_K_ROW: return "row_kernel";
+        case CKPT_K_ROW: return "tile_rows_kernel";
         default: return nullptr;
     }
 }
@@ -1247,11 +1753,14 @@ int ckpt_check_inputs(const void* workspace, int L, int M, int B, void* stream, 
         workspace = dev ? ensure_scratch(*dev) : nullptr;
         if (!workspace) return CKPT_E_HIP;
     }
-    const Workspace ws = carve(const_cast<void*>(workspace), L, B);
+    const Workspace ws = carve(const_cast<void*>(workspace), L, int(ckpt_row_pitch(M)), B);
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (!hip_ok(hipMemcpyAsync(flags_host, ws.flags, size_t(B) * sizeof(int32_t), hipMemcpyDeviceToHost, st)))
         return CKPT_E_HIP;
+    int32_t fault = 0;
+    if (!hip_ok(hipMemcpyAsync(&fault, ws.fault, sizeof(int32_t), hipMemcpyDeviceToHost, st))) return CKPT_E_HIP;
     if (!hip_ok(hipStreamSynchronize(st))) return CKPT_E_HIP;
+    if (fault) return CKPT_E_INTERNAL;
     for (int b = 0; b < B; ++b)
         if (flags_host[b]) return CKPT_E_INPUT;
     return CKPT_OK;

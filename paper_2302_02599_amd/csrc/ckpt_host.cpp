@@ -51,6 +51,7 @@ const char* ckpt_strerror(int code) {
         case CKPT_E_INPUT: return "chain values violate the preconditions";
         case CKPT_E_CORRUPT: return "arg table or operation list is inconsistent";
         case CKPT_E_NOTREADY: return "helper streams do not exist yet and cannot be created now: call ckpt_init first";
+        case CKPT_E_INTERNAL: return "a wait between work-groups of the fill expired; the tables are incomplete";
         default: return "unknown error";
     }
 }

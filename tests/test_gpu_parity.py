@@ -150,8 +150,8 @@ def _same_tables(a, b, M):
 @pytest.mark.parametrize("which", ["cfg2", "wide"])
 def test_tables_do_not_depend_on_the_schedule(amd, oracle_mod, which):
     """The same input under every work order the library can take: one stream or 2, 3, 4 groups of
-    chains (the library's helper streams or the caller's), and 1, 2 or 4 waves per list of splits
-    in the block-product kernel.  Every variant must give the tables of the plain call, bit for bit
+    chains (the library's helper streams or the caller's), 1, 2 or 4 waves per list of splits
+    in the block-product kernel, and the rows of a block diagonal in one launch or in seven.  Every variant must give the tables of the plain call, bit for bit
     (and those equal the oracle's, checked on one chain)."""
     import torch
     batch = make_config(2) if which == "cfg2" else \
@@ -165,7 +165,8 @@ def test_tables_do_not_depend_on_the_schedule(amd, oracle_mod, which):
                 dict(groups=1, list_split=1), dict(groups=1, list_split=2), dict(groups=1, list_split=4),
                 dict(groups=4, list_split=2), dict(groups=2, list_split=4),
                 dict(groups=4, side_streams=[s.cuda_stream for s in own]),
-                dict(groups=3, list_split=1, side_streams=[s.cuda_stream for s in own[:2]])]
+                dict(groups=3, list_split=1, side_streams=[s.cuda_stream for s in own[:2]]),
+                dict(row_launches=1), dict(groups=1, row_launches=1), dict(groups=4, row_launches=1, list_split=2)]
     for opts in variants:
         print(f"case {batch.name} {opts}", flush=True)
         other = amd.solve(batch, **opts)
