@@ -748,19 +748,20 @@ __global__ void __launch_bounds__(kRowWG) row_kernel(Ctx c, int D) {
 constexpr uint32_t kNoRead = 0xfffffff0u;  // buffer offset beyond any table: the load returns 0, no access
 constexpr int kSpinLimit = 1 << 20;        // polls of a wait before it gives up (seconds, never reached)
 
-__device__ __forceinline__ uint32_t ld32_dev(rsrc_t tab, uint32_t elem, uint32_t off) {  // device-scope load
-    return uint32_t(__builtin_amdgcn_raw_buffer_load_b32(tab, int(off), int(elem << 2), 16));
-}
 
 // Per-tile parameters of the row kernel, fetched once into LDS by the whole work-group: the
-// rows' thresholds and frontier, prefix sums, shifts.  Inside the row steps nothing but table
-// cells comes from memory, so a step costs one memory round trip.
+// rows' thresholds and frontier, prefix sums, shifts, and the byte offsets of the table rows the
+// tile touches.  Inside the row steps nothing but table cells comes from memory, so a step
+// costs one memory round trip, and an address is one add: every access is
+// descriptor base + per-lane offset (row offset from here + 4 m - 4 shift) + cc * row pitch.
 struct TilePar {
     int32_t mall[kT][kT], mnull[kT][kT], need[kT][kT];  // [r][cc]: cell (i0 + r, j_cc)
-    int32_t Pi[kT + 1];   // P[i0 + u], u = 0..8
-    int32_t Pj[kT];       // P[min(jb + c2 + 1, L - 1)]
-    int32_t wsh[kT + 1];  // shift of split q = i0 + u
+    int32_t Pi[kT + 1];       // P[i0 + u], u = 0..8
+    int32_t Pj[kT];           // P[min(jb + c2 + 1, L - 1)]
+    int32_t wsh[kT + 1];      // shift of split q = i0 + u
     int32_t wabs[kT], fb[kT];
+    uint32_t rowoff[kT + 1];  // byte offset of cell (i0 + u, jb) in the chain's cost table, u = 0..8
+    uint32_t diagoff[kT];     // byte offset of cell (i0 + r, i0 + r)
 };
 
 template <int DC>
@@ -768,12 +769,9 @@ struct TileCtx {
     Ctx c;
     const TilePar* par;
     int b, I, J, L, pitch, i0, jb, cend, band;
-    size_t chain;
-    rsrc_t tab;
-    const int32_t* P;
-    const int32_t* wsh;
+    rsrc_t tab, atab;  // the chain's cost table (bytes) and candidate table
     uint32_t m, moff;
-    int jc[kT];
+    uint32_t col4[kT];  // cc * pitch * 4: the scalar part of every address
     int32_t* prog;    // progress of this tile: [chunks of 64 columns]
     int chunk0;       // first chunk of this band
     int nwait;        // chunks below the band that this wave's shifted reads can reach
@@ -786,6 +784,15 @@ struct TileCtx {
     uint32_t ri[kT + 1][kT];
     uint32_t rj[kT][kT];
 };
+
+// Table accesses of the row kernel: voff = per-lane byte offset (kNoRead: nothing is read, the
+// result is 0), soff = wave-uniform byte offset.  dev = device scope.
+__device__ __forceinline__ uint32_t tld(rsrc_t tab, uint32_t voff, uint32_t soff) {
+    return uint32_t(__builtin_amdgcn_raw_buffer_load_b32(tab, int(voff), int(soff), 0));
+}
+__device__ __forceinline__ uint32_t tld_dev(rsrc_t tab, uint32_t voff, uint32_t soff) {
+    return uint32_t(__builtin_amdgcn_raw_buffer_load_b32(tab, int(voff), int(soff), 16));
+}
 
 // Requests the progress of the chunks below the band (lane k looks at chunk chunk0 - 1 - k);
 // consumed by the next wait_rows_below, by which time the load has long returned.
@@ -817,26 +824,26 @@ __device__ __forceinline__ void wait_rows_below(TileCtx<DC>& x, int rows) {
     }
 }
 
-// Cell (q, jb + cc) of a row finished in THIS launch, at column m - sh: from LDS if that column
-// lies in this band (`below` = the row's buffer), else from the table with a device-scope load.
+// Cells (i0 + u, jb + cc), cc = first_cc .. cend - 1, of a row finished in THIS launch, at column
+// m - sh: from LDS if that column lies in this band (`below` = the row's buffer), else from the
+// table with a device-scope load.
 // D >= 2: the cells of the tile hold the gemm's partial minima, marked by bit 31, until their
 // row is finished, so the read needs no flag: a lane that finds the mark reads again (bounded).
 // D < 2: the caller has waited for the progress flags of the chunks that are read.
-template <int DC>
-__device__ __forceinline__ void read_row_below(TileCtx<DC>& x, const uint32_t (*below)[kBand], int q, uint32_t sh,
-                                               int first_cc, uint32_t (&out)[kT]) {
+template <int DC, bool FULL>
+__device__ __forceinline__ void read_row_below(TileCtx<DC>& x, const uint32_t (*below)[kBand], uint32_t rowoff,
+                                               uint32_t sh, int first_cc, uint32_t (&out)[kT]) {
+    const int cend = FULL ? kT : x.cend;
     const int t = int(threadIdx.x) - int(sh);  // column inside the band
     const bool in_band = t >= 0;
-    const uint32_t off = (!in_band && x.m >= sh) ? x.moff : kNoRead;
-    const uint32_t rq = uint32_t(row_base(x.L, q));
+    const uint32_t voff = (!in_band && x.m >= sh) ? x.moff + rowoff - 4 * sh : kNoRead;
     uint32_t mem[kT];
     auto fetch = [&]() {
         uint32_t marks = 0;
 #pragma unroll
         for (int cc = 0; cc < kT; ++cc) {
             mem[cc] = 0;
-            if (cc >= first_cc && cc < x.cend)  // only cells that exist are read
-                mem[cc] = ld32_dev(x.tab, (rq + uint32_t(x.jb + cc)) * uint32_t(x.pitch) - sh, off);
+            if (cc >= first_cc && cc < cend) mem[cc] = tld_dev(x.tab, voff, x.col4[cc]);  // only cells that exist
             marks |= mem[cc];
         }
         return (marks >> 31) != 0;
@@ -858,14 +865,16 @@ __device__ __forceinline__ void read_row_below(TileCtx<DC>& x, const uint32_t (*
     }
 #pragma unroll
     for (int cc = 0; cc < kT; ++cc) {
-        if (cc >= first_cc && cc < x.cend) {
+        if (cc >= first_cc && cc < cend) {
             const uint32_t lds = below[cc][in_band ? t : 0];
             out[cc] = in_band ? lds : mem[cc];
         }
     }
 }
 
-template <int DC, int R, bool CNT>
+// FULL: the tile has all eight columns (always, except in the last column block of a chain whose
+// length is not a multiple of eight); the tests for columns that do not exist then vanish.
+template <int DC, int R, bool CNT, bool FULL>
 __device__ __forceinline__ void tile_row(TileCtx<DC>& x, uint32_t (*s_row)[kT][kBand]) {
     constexpr int T = kT;
     constexpr int RF = (DC == 2) ? T - 2 : T - 1;                      // first row this kernel finishes
@@ -873,13 +882,13 @@ __device__ __forceinline__ void tile_row(TileCtx<DC>& x, uint32_t (*s_row)[kT][k
     constexpr int NQ = (DC == 0) ? 0 : (DC == 1 ? T - R : T - 1 - R);  // splits in the row block (D = 1: and q = jb)
     constexpr int NQA = NQ > 0 ? NQ : 1;
     constexpr int U = R + 1;                                           // the row below
-    const int L = x.L, pitch = x.pitch;
+    const int L = x.L;
+    const int cend = FULL ? T : x.cend;
     const int i = x.i0 + R;
     if (i >= L) return;  // ragged last block: uniform over the work-group
     const bool below_here = R < RF && i + 1 < L;  // the row below exists and belongs to this launch
     const uint32_t m = x.m, moff = x.moff;
     const TilePar& par = *x.par;
-    const int rowi = tri_row(L, i, i) - i;  // + j = row of (i, j)
     const uint32_t (*below)[kBand] = s_row[U & 1];
     uint32_t (*mine)[kBand] = s_row[R & 1];
     uint32_t val[T];
@@ -891,16 +900,14 @@ __device__ __forceinline__ void tile_row(TileCtx<DC>& x, uint32_t (*s_row)[kT][k
         // ---- loads of this row, all issued together ----
         // the operands that the row below contributes to all rows above it, kept
         if ((U < T || DC == 1) && x.i0 + U < L) {
-            const int q = x.i0 + U;
             const uint32_t sh = uint32_t(par.wsh[U]);
             if (below_here) {
-                read_row_below(x, below, q, sh, DC == 0 ? U : 0, x.ri[U]);
+                read_row_below<DC, FULL>(x, below, par.rowoff[U], sh, DC == 0 ? U : 0, x.ri[U]);
             } else {  // finished by an earlier launch
-                const uint32_t off = m >= sh ? moff : kNoRead;
+                const uint32_t voff = m >= sh ? moff + par.rowoff[U] - 4 * sh : kNoRead;
 #pragma unroll
                 for (int cc = (DC == 0 ? U : 0); cc < T; ++cc)
-                    if (cc < x.cend)
-                        x.ri[U][cc] = ld32(x.tab, uint32_t(row_base(L, q) + x.jb + cc) * uint32_t(pitch) - sh, off);
+                    if (cc < cend) x.ri[U][cc] = tld(x.tab, voff, x.col4[cc]);
             }
         }
         int row_need = 1 << 30;
@@ -909,37 +916,37 @@ __device__ __forceinline__ void tile_row(TileCtx<DC>& x, uint32_t (*s_row)[kT][k
             row_need = min(row_need, DC == 2 ? par.need[R][cc] : min(par.mall[R][cc], par.mnull[R][cc]));
         const int m_hi = __builtin_amdgcn_readfirstlane(int(m)) | 63;
         const bool live = m_hi >= row_need;  // else the whole chunk lies below the feasibility frontier of the row
-        const unsigned cols = unsigned(max(0, x.cend - CF));  // cells of the row that exist
+        const unsigned cols = unsigned(max(0, cend - CF));  // cells of the row that exist
         count_work<CNT>(x.c.work, 2, cols + (live ? unsigned(NQ) + (DC == 2 ? 10u : 0u) + cols : 0u), cols);
         const uint32_t Pi = par.Pi[R];
         const uint32_t fbi = par.fb[R];
         const uint32_t wabi = par.wabs[R];
+        const uint32_t own = moff + par.rowoff[R];  // this lane's cell of the row, column block start
         uint32_t nl[NQA], pc[T], pp[T], al[T];
 #pragma unroll
         for (int cc = 0; cc < T; ++cc) al[cc] = 0, pc[cc] = 0xffffffffu, pp[cc] = 0;
         if (live) {
+            const uint32_t left = moff + par.diagoff[R];  // cell (i, i); (i, i + u) is u rows further
 #pragma unroll
-            for (int u = 0; u < NQ; ++u) nl[u] = ld32(x.tab, uint32_t(rowi + i + u) * uint32_t(pitch), moff);
-            if (DC == 2) {  // gemm partial
+            for (int u = 0; u < NQ; ++u) nl[u] = tld(x.tab, left, x.col4[u]);
+            if (DC == 2) {  // gemm partial; bit 31 marks it
 #pragma unroll
                 for (int cc = 0; cc < T; ++cc) {
-                    const size_t o = x.chain + size_t(rowi + x.jc[cc]) * pitch + m;
-                    pc[cc] = uint32_t(x.c.cost[o]) & 0x7fffffffu;  // bit 31 marks the gemm's partial minima
-                    pp[cc] = x.c.arg[o];
+                    if (cc < cend) {
+                        pc[cc] = tld(x.tab, own, x.col4[cc]) & 0x7fffffffu;
+                        pp[cc] = uint32_t(__builtin_amdgcn_raw_buffer_load_b8(x.atab, int(own >> 2), int(x.col4[cc] >> 2), 0));
+                    }
                 }
             }
             // C_all: cell (i + 1, j) at m - omega_abar^{i+1}, for j > i
             if (below_here) {
-                read_row_below(x, below, i + 1, wabi, DC == 0 ? CF + 1 : CF, al);
+                read_row_below<DC, FULL>(x, below, par.rowoff[U], wabi, DC == 0 ? CF + 1 : CF, al);
             } else if (i + 1 < L) {  // row 0 of the tile below, or row 7 finished by the gemm: earlier launches
-                const uint32_t off = m >= wabi ? moff : kNoRead;
+                const uint32_t voff = m >= wabi ? moff + par.rowoff[U] - 4 * wabi : kNoRead;
 #pragma unroll
                 for (int cc = (DC == 0 ? CF + 1 : CF); cc < T; ++cc)
-                    if (cc < x.cend)
-                        al[cc] = ld32(x.tab, uint32_t(row_base(L, i + 1) + x.jb + cc) * uint32_t(pitch) - wabi, off);
+                    if (cc < cend) al[cc] = tld(x.tab, voff, x.col4[cc]);
             }
-        }
-        if (live) {
             // ---- evaluation, in candidate-number order with strict '<' ----
             uint32_t best[T], pick[T];
 #pragma unroll
@@ -978,19 +985,18 @@ __device__ __forceinline__ void tile_row(TileCtx<DC>& x, uint32_t (*s_row)[kT][k
             }
 #pragma unroll
             for (int cc = CF; cc < T; ++cc) {
-                if (cc < x.cend) {
-                    const size_t o = x.chain + size_t(rowi + x.jc[cc]) * pitch + m;
-                    __hip_atomic_store(x.c.cost + o, int32_t(val[cc]), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    x.c.arg[o] = uint8_t(pick[cc]);
+                if (cc < cend) {  // cost with a device-scope store: other bands read it in this launch
+                    __builtin_amdgcn_raw_buffer_store_b32(int(val[cc]), x.tab, int(own), int(x.col4[cc]), 16);
+                    __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(pick[cc]), x.atab, int(own >> 2),
+                                                         int(x.col4[cc] >> 2), 0);
                 }
             }
         } else {
 #pragma unroll
             for (int cc = CF; cc < T; ++cc) {
-                if (cc < x.cend) {
-                    const size_t o = x.chain + size_t(rowi + x.jc[cc]) * pitch + m;
-                    __hip_atomic_store(x.c.cost + o, int32_t(kInf), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    x.c.arg[o] = 0;
+                if (cc < cend) {
+                    __builtin_amdgcn_raw_buffer_store_b32(int(kInf), x.tab, int(own), int(x.col4[cc]), 16);
+                    __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(0), x.atab, int(own >> 2), int(x.col4[cc] >> 2), 0);
                 }
             }
         }
@@ -1013,11 +1019,11 @@ __device__ __forceinline__ void tile_row(TileCtx<DC>& x, uint32_t (*s_row)[kT][k
     if (R > 0) __syncthreads();  // the row is in LDS for the waves of this band
 }
 
-template <int DC, int R, bool CNT>
+template <int DC, int R, bool CNT, bool FULL>
 struct TileRows {
     static __device__ __forceinline__ void run(TileCtx<DC>& x, uint32_t (*s_row)[kT][kBand]) {
-        tile_row<DC, R, CNT>(x, s_row);
-        if constexpr (R > 0) TileRows<DC, R - 1, CNT>::run(x, s_row);
+        tile_row<DC, R, CNT, FULL>(x, s_row);
+        if constexpr (R > 0) TileRows<DC, R - 1, CNT, FULL>::run(x, s_row);
     }
 };
 
@@ -1048,16 +1054,15 @@ __global__ void __launch_bounds__(kRowWG, 3) tile_rows_kernel(Ctx c, int D, int3
     x.i0 = x.I * T;
     x.jb = x.J * T;
     x.cend = min(T, c.L - x.jb);
-    x.chain = size_t(x.b) * c.rows * c.pitch;
-    x.tab = table_rsrc(c.cost + x.chain, uint32_t(c.rows) * uint32_t(c.pitch) * 4u);
-    x.P = c.ws.P + size_t(x.b) * (c.L + 1);
-    x.wsh = c.ws.wsh + size_t(x.b) * c.L;
+    const size_t chain = size_t(x.b) * c.rows * c.pitch;
+    x.tab = table_rsrc(c.cost + chain, uint32_t(c.rows) * uint32_t(c.pitch) * 4u);
+    x.atab = __builtin_amdgcn_make_buffer_rsrc(c.arg + chain, 0, int(uint32_t(c.rows) * uint32_t(c.pitch)), 0x00020000);
     x.m = uint32_t(x.band) * kBand + threadIdx.x;
     x.moff = x.m * 4;
     x.seen = 0;
     x.dead = s_fault != 0;  // an earlier work-group gave up: drain
 #pragma unroll
-    for (int cc = 0; cc < T; ++cc) x.jc[cc] = min(x.jb + cc, c.L - 1);
+    for (int cc = 0; cc < T; ++cc) x.col4[cc] = uint32_t(cc) * uint32_t(c.pitch) * 4u;
 #pragma unroll
     for (int u = 0; u <= T; ++u)
 #pragma unroll
@@ -1066,6 +1071,8 @@ __global__ void __launch_bounds__(kRowWG, 3) tile_rows_kernel(Ctx c, int D, int3
     for (int c2 = 0; c2 < T; ++c2)
 #pragma unroll
         for (int cc = 0; cc < T; ++cc) x.rj[c2][cc] = 0;
+    const int32_t* P = c.ws.P + size_t(x.b) * (c.L + 1);
+    const int32_t* wsh = c.ws.wsh + size_t(x.b) * c.L;
     {   // parameters of the tile: one fetch by the whole work-group
         const int t = threadIdx.x, L = c.L;
         const size_t bL = size_t(x.b) * L;
@@ -1077,13 +1084,16 @@ __global__ void __launch_bounds__(kRowWG, 3) tile_rows_kernel(Ctx c, int D, int3
             s_par.need[r][t & 7] = DC == 2 ? c.ws.need[at] : 0;  // D < 2 runs beside the frontier kernel
         } else if (t < 64 + T + 1) {
             const int u = t - 64, q = min(x.i0 + u, L - 1);
-            s_par.Pi[u] = x.P[min(x.i0 + u, L)];
-            s_par.wsh[u] = x.wsh[q];
+            s_par.Pi[u] = P[min(x.i0 + u, L)];
+            s_par.wsh[u] = wsh[q];
+            // cell (q, jb); on the diagonal tile only the cells with jb + cc >= q exist and are touched
+            s_par.rowoff[u] = uint32_t(row_base(L, q) + x.jb) * uint32_t(c.pitch) * 4u;
         } else if (t >= 96 && t < 96 + T) {
             const int r = t - 96, q = min(x.jb + r + 1, L - 1), i = min(x.i0 + r, L - 1);
-            s_par.Pj[r] = x.P[q];
+            s_par.Pj[r] = P[q];
             s_par.wabs[r] = c.ws.wabs[bL + i];
             s_par.fb[r] = c.ws.fb[bL + i];
+            s_par.diagoff[r] = uint32_t(row_base(L, i) + i) * uint32_t(c.pitch) * 4u;
         }
     }
     x.par = &s_par;
@@ -1103,17 +1113,21 @@ __global__ void __launch_bounds__(kRowWG, 3) tile_rows_kernel(Ctx c, int D, int3
     if (DC >= 1 && !x.dead && !x.idle) {
         // operands of the splits in the column block, finished by earlier launches
 #pragma unroll
-        for (int cc = 1; cc < T; ++cc)
+        for (int c2 = 0; c2 < T - 1; ++c2) {
+            const int q = min(x.jb + c2 + 1, c.L - 1);
+            const uint32_t sh = uint32_t(wsh[q]);
+            const uint32_t voff =
+                x.m >= sh ? x.moff + uint32_t(row_base(c.L, q) + x.jb) * uint32_t(c.pitch) * 4u - 4 * sh : kNoRead;
 #pragma unroll
-            for (int c2 = 0; c2 < cc; ++c2) {
-                const int q = min(x.jb + c2 + 1, c.L - 1);
-                const uint32_t sh = uint32_t(x.wsh[q]);
-                x.rj[c2][cc] = ld32(x.tab, uint32_t(row_base(c.L, q) + x.jc[cc]) * uint32_t(c.pitch) - sh,
-                                    x.m >= sh ? x.moff : kNoRead);
-            }
+            for (int cc = c2 + 1; cc < T; ++cc)
+                if (cc < x.cend) x.rj[c2][cc] = tld(x.tab, voff, x.col4[cc]);
+        }
         count_work<CNT>(c.work, 2, 28u, 0);
     }
-    TileRows<DC, RF, CNT>::run(x, s_row);
+    if (x.cend == T)
+        TileRows<DC, RF, CNT, true>::run(x, s_row);
+    else
+        TileRows<DC, RF, CNT, false>::run(x, s_row);
 }
 
 using RowFn = void (*)(Ctx, int);
