@@ -363,6 +363,7 @@ def main():
     ap.add_argument("--row-launches", type=int, default=0, help="experiment: 1 = one launch per tile row")
     ap.add_argument("--list-split", type=int, default=0, help="experiment: waves per work list, 0 automatic")
     ap.add_argument("--stagger", type=int, default=0, help="experiment: phase-shift half of the chain groups")
+    ap.add_argument("--frontier", type=int, default=0, help="experiment: 1 always run the exact frontier, 2 never")
     a = ap.parse_args()
     if a.gpus != 1:
         print("bench.py: this build solves on one GPU; chains would be split across GPUs with no "
@@ -382,8 +383,9 @@ def main():
         torch.cuda.synchronize()
         del src, dst
     sched = None
-    if a.groups or a.row_launches or a.list_split or a.stagger:
-        sched = dict(groups=a.groups, row_launches=a.row_launches, list_split=a.list_split, stagger=a.stagger)
+    if a.groups or a.row_launches or a.list_split or a.stagger or a.frontier:
+        sched = dict(groups=a.groups, row_launches=a.row_launches, list_split=a.list_split, stagger=a.stagger,
+                     frontier=a.frontier)
 
     r = run_config(amd, a.config, a.steps, a.warmup, dev, sched=sched)
     batch = r["batch"]

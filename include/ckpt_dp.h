@@ -151,6 +151,15 @@ int ckpt_solve_batched(const ckpt_chains_t* chains, int L, int M, int B, void* s
  *                 every launch of the block-product kernel.
  *   row_launches  0: the rows of all tiles of a block diagonal are finished by one launch whose
  *                 work-groups wait for each other's rows.  1: one launch per row of the tiles.
+ *   stagger       1: half of the groups start their first block product when the first group has
+ *                 finished its own (an experiment: the phases of the groups then alternate).
+ *   frontier      0: automatic.  1: always run the kernel that computes the exact feasibility
+ *                 frontier.  2: never (the fill then prunes with the weaker bound
+ *                 min(m_all, m_null) only).
+ *   spin_limit    0: default.  > 0: polls after which a wait of one work-group for another gives up.
+ *                 < 0: every such wait gives up at once -- for tests of the failure path: the
+ *                 kernels still end normally, the tables are incomplete and ckpt_check_inputs
+ *                 returns CKPT_E_INTERNAL.
  *   reserved      zeros
  * opts == NULL is ckpt_solve_batched.  Returns as ckpt_solve_batched, plus CKPT_E_NOTREADY
  * when groups > 1 is requested while `stream` is being captured and ckpt_init has not run.
@@ -161,7 +170,9 @@ typedef struct ckpt_solve_opts {
     int list_split;
     int row_launches;
     int stagger;
-    int reserved[1];
+    int frontier;
+    int spin_limit;
+    int reserved[3];
 } ckpt_solve_opts_t;
 int ckpt_solve_batched_opts(const ckpt_chains_t* chains, int L, int M, int B, void* stream, int32_t* cost,
                             uint8_t* arg, void* workspace, const ckpt_solve_opts_t* opts);

@@ -36,7 +36,8 @@ class _Op(ctypes.Structure):
 
 class _SolveOpts(ctypes.Structure):
     _fields_ = [("groups", ctypes.c_int), ("side_streams", ctypes.c_void_p * 3), ("list_split", ctypes.c_int),
-                ("row_launches", ctypes.c_int), ("stagger", ctypes.c_int), ("reserved", ctypes.c_int * 1)]
+                ("row_launches", ctypes.c_int), ("stagger", ctypes.c_int), ("frontier", ctypes.c_int), ("spin_limit", ctypes.c_int),
+                ("reserved", ctypes.c_int * 3)]
 
 
 def lib_path() -> str:
@@ -192,12 +193,13 @@ def ckpt_init(device: int = -1) -> None:
 
 
 def ckpt_solve_batched_opts(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, *, groups=0, side_streams=None,
-                            list_split=0, row_launches=0, stagger=0, wdelta=None, of=None, ob=None, stream=None) -> None:
+                            list_split=0, row_launches=0, stagger=0, frontier=0, spin_limit=0, wdelta=None, of=None, ob=None, stream=None) -> None:
     """ckpt_solve_batched with the schedule chosen by the caller: number of chain groups (1 = no
     helper streams), caller-owned side streams (raw hipStream_t values), waves per work list."""
     ch, st = _marshal(uf, ub, wa, wabar, L, M, B, cost, arg, workspace, wdelta, of, ob, stream)
     opts = _SolveOpts()
     opts.groups, opts.list_split, opts.row_launches, opts.stagger = groups, list_split, row_launches, stagger
+    opts.frontier, opts.spin_limit = frontier, spin_limit
     for k, h in enumerate(side_streams or []):
         opts.side_streams[k] = h
     rc = load_library().ckpt_solve_batched_opts(ctypes.byref(ch), L, M, B, st, cost.data_ptr(), arg.data_ptr(),

@@ -129,6 +129,7 @@ inline Workspace carve(void* base, int L, int pitch, int B) {
 struct Ctx {
     int L, M, pitch, rows;
     int b0;  // first chain of this launch; blockIdx.z counts from it
+    int spin_limit;  // polls before a wait between work-groups gives up; < 0: every such wait gives up at once
     Workspace ws;
     int32_t* cost;
     uint8_t* arg;
@@ -231,13 +232,19 @@ __global__ void __launch_bounds__(256) precompute_kernel(ckpt_chains_t ch, int L
         int sweep = s_wa[s] + ofs;  // omega_a^s + o_f^s, then max over s+1 <= j < t
         int32_t* mall = ws.mall + (size_t(b) * L + s0) * L;
         int32_t* mnull = ws.mnull + (size_t(b) * L + s0) * L;
+        int32_t* need = ws.need + (size_t(b) * L + s0) * L;
         for (int t = s; t <= L; ++t) {
             if (t >= s + 2) {
                 const int j = t - 1;
                 sweep = max(sweep, s_wa[j - 1] + s_wa[j] + s_of[j - 1]);
             }
-            mall[t - 1] = max(s_wd[t] + abar + ofs, s_wd[s] + abar + obs);
-            mnull[t - 1] = s_wd[t] + sweep;
+            const int keep = max(s_wd[t] + abar + ofs, s_wd[s] + abar + obs), ck = s_wd[t] + sweep;
+            mall[t - 1] = keep;
+            mnull[t - 1] = ck;
+            // A first, weak feasibility frontier: a finite cell passes at least one of its two gates.
+            // The frontier kernel overwrites it with the exact one while the fill already runs;
+            // whichever value a reader sees is a valid lower bound.
+            need[t - 1] = min(keep, ck);
         }
     }
 }
@@ -652,13 +659,13 @@ __global__ void __launch_bounds__(kRowWG) row_kernel(Ctx c, int D) {
     // A wave whose whole chunk lies below the feasibility frontier of every cell of the row
     // stores "infeasible" and reads nothing.
     {
-        // D >= 2: the frontier.  D < 2 runs while the frontier is still being computed and uses the
-        // weaker bound min(m_all, m_null): a finite cell passes at least one of its two gates.
+        // the frontier as far as it is known: the weak one of the precompute kernel (a finite cell
+        // passes at least one of its two gates) until the frontier kernel has written the exact one
         const int32_t* need = c.ws.need + (size_t(b) * L + i) * L;
         int row_need = 1 << 30;
 #pragma unroll
         for (int cc = CF; cc < T; ++cc)
-            row_need = min(row_need, DC == 2 ? need[jc[cc]] : min(mall[jc[cc]], mnull[jc[cc]]));
+            row_need = min(row_need, need[jc[cc]]);
         const int m_hi = __builtin_amdgcn_readfirstlane(int(m)) | 63;
         if (m_hi < row_need) {
 #pragma unroll
@@ -746,7 +753,7 @@ __global__ void __launch_bounds__(kRowWG) row_kernel(Ctx c, int D) {
 // lane 7 x 8 + 28 + 64 operand loads instead of the 252 + 224 + 64 of one launch per row.
 // ---------------------------------------------------------------------------
 constexpr uint32_t kNoRead = 0xfffffff0u;  // buffer offset beyond any table: the load returns 0, no access
-constexpr int kSpinLimit = 1 << 20;        // polls of a wait before it gives up (seconds, never reached)
+constexpr int kSpinLimit = 1 << 20;        // default polls of a wait before it gives up (seconds, never reached)
 
 
 // Per-tile parameters of the row kernel, fetched once into LDS by the whole work-group: the
@@ -807,8 +814,8 @@ template <int DC>
 __device__ __forceinline__ void wait_rows_below(TileCtx<DC>& x, int rows) {
     if (x.nwait == 0 || x.dead) return;
     const int lane = threadIdx.x & 63;
-    bool ok = __all(lane >= x.nwait || x.seen >= rows) && x.nwait <= 64;
-    for (int spin = 0; !ok && spin < kSpinLimit; ++spin) {
+    bool ok = __all(lane >= x.nwait || x.seen >= rows) && x.nwait <= 64 && x.c.spin_limit >= 0;
+    for (int spin = 0; !ok && spin < x.c.spin_limit; ++spin) {
         ok = true;
         for (int k = lane; k < x.nwait; k += 64)
             ok = ok && __hip_atomic_load(x.prog + x.chunk0 - 1 - k, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) >= rows;
@@ -851,8 +858,9 @@ __device__ __forceinline__ void read_row_below(TileCtx<DC>& x, const uint32_t (*
     bool again = fetch();
     if (DC == 2) {
         int spin = 0;
+        if (x.c.spin_limit < 0) again = !in_band && x.m >= sh;  // forced: every read from another band gives up
         while (__any(again)) {  // some lane met a cell that its owner has not finished yet
-            if (++spin > kSpinLimit ||
+            if (++spin > x.c.spin_limit ||
                 ((spin & 63) == 0 && __hip_atomic_load(x.c.ws.fault, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0)) {
                 x.dead = true;
                 if ((threadIdx.x & 63) == 0)
@@ -913,7 +921,7 @@ __device__ __forceinline__ void tile_row(TileCtx<DC>& x, uint32_t (*s_row)[kT][k
         int row_need = 1 << 30;
 #pragma unroll
         for (int cc = CF; cc < T; ++cc)
-            row_need = min(row_need, DC == 2 ? par.need[R][cc] : min(par.mall[R][cc], par.mnull[R][cc]));
+            row_need = min(row_need, par.need[R][cc]);
         const int m_hi = __builtin_amdgcn_readfirstlane(int(m)) | 63;
         const bool live = m_hi >= row_need;  // else the whole chunk lies below the feasibility frontier of the row
         const unsigned cols = unsigned(max(0, cend - CF));  // cells of the row that exist
@@ -1081,7 +1089,7 @@ __global__ void __launch_bounds__(kRowWG, 3) tile_rows_kernel(Ctx c, int D, int3
             const size_t at = (bL + i) * L + min(x.jb + (t & 7), L - 1);  // no dynamic index into x: it stays in registers
             s_par.mall[r][t & 7] = c.ws.mall[at];
             s_par.mnull[r][t & 7] = c.ws.mnull[at];
-            s_par.need[r][t & 7] = DC == 2 ? c.ws.need[at] : 0;  // D < 2 runs beside the frontier kernel
+            s_par.need[r][t & 7] = c.ws.need[at];  // weak or exact, whichever is there: both are lower bounds
         } else if (t < 64 + T + 1) {
             const int u = t - 64, q = min(x.i0 + u, L - 1);
             s_par.Pi[u] = P[min(x.i0 + u, L)];
@@ -1506,6 +1514,9 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     if (row_mode != 0 && row_mode != 1) return CKPT_E_ARG;
     const bool fused_rows = row_mode == 0;
     const int stagger = opts ? opts->stagger : 0;
+    const int frontier_mode = opts ? opts->frontier : 0;
+    const int spin_limit = opts && opts->spin_limit ? opts->spin_limit : kSpinLimit;
+    if (frontier_mode < 0 || frontier_mode > 2) return CKPT_E_ARG;
     unsigned long long* work = prof ? prof->work : nullptr;
     if (want_groups < 0 || want_groups > kSideStreams + 1) return CKPT_E_ARG;
     if (want_ks != 0 && want_ks != 1 && want_ks != 2 && want_ks != 4) return CKPT_E_ARG;
@@ -1529,13 +1540,15 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
     // Several streams.  Chains are independent, so from D = 2 on the batch is split in up to four
     // groups that run the same launch sequence on as many streams: the many short row launches
     // of one group overlap with work of the others instead of leaving the machine idle between
-    // dependent launches.  Before that, the frontier (a few busy CUs for a long time) runs on
-    // the first side stream next to the D = 0 and D = 1 rows of the whole batch, which do not
-    // need it.  The side streams are forked from and joined back into the caller's stream with
-    // events.  Small problems are bound by launch latency, where more streams only add launches.
+    // dependent launches.  The frontier kernel (a few busy CUs for a long time) runs on the first
+    // side stream beside everything else: the fill prunes with whatever frontier is in memory,
+    // the weak one of the precompute kernel or the exact one.  The side streams are forked from
+    // and joined back into the caller's stream with events.  Small problems are bound by launch
+    // latency, where more streams only add launches.
     // Automatic choice: split when the batch is large enough to be bound by the GPU and not by
     // launch latency (where more streams only add launches).  The caller can force either way.
     const bool large = B >= 2 && size_t(B) * nblk * pitch >= (size_t(1) << 19);
+
     int groups = want_groups ? want_groups : (large ? kSideStreams + 1 : 1);
     groups = std::min(groups, B);
     if (prof || nblk < 3) groups = 1;  // the event trail times one stream; no diagonal to split
@@ -1557,6 +1570,11 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
         }
     }
     Device* side = groups > 1 ? dev : nullptr;
+    // The exact frontier costs one long single-block launch per chain (about 2 us per stage).  On
+    // a side stream it runs beside the fill for free; on the caller's stream it pays only when
+    // the pruning it adds (about a third of the block products) saves more than it costs.
+    const bool want_frontier =
+        frontier_mode == 1 || (frontier_mode == 0 && (groups > 1 || size_t(B) * pitch * nblk * nblk >= 6000000));
     std::unique_lock<std::mutex> lock;
     if (side) lock = std::unique_lock<std::mutex>(side->busy);  // one fork/join at a time per device
     hipStream_t gs[kSideStreams + 1] = {st, st, st, st};  // stream of group g
@@ -1579,12 +1597,14 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
                 return CKPT_E_HIP;
             forked = 1;
         }
-        hipLaunchKernelGGL(frontier_kernel, dim3(B), dim3(1024), frontier_lds, gs[1], *chains, L, ws);
-        CKPT_AFTER_LAUNCH(CKPT_K_FRONTIER);
+        if (want_frontier) {
+            hipLaunchKernelGGL(frontier_kernel, dim3(B), dim3(1024), frontier_lds, gs[1], *chains, L, ws);
+            CKPT_AFTER_LAUNCH(CKPT_K_FRONTIER);
+        }
 
         const int nbands = bands_of(pitch);
         for (int D = 0; D < 2 && D < nblk; ++D) {
-            const Ctx ctx{L, M, pitch, rows, 0, ws, cost, arg, work};
+            const Ctx ctx{L, M, pitch, rows, 0, spin_limit, ws, cost, arg, work};
             if (fused_rows) {
                 const dim3 grid(nbands, nblk - D, B);
                 int32_t* tick = ws.tick + D * kTickGroups;
@@ -1601,8 +1621,9 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
             }
         }
         if (side) {
-            // the caller's stream waits for the frontier, every side stream for the D < 2 rows
-            if (!join_side(0) || !hip_ok(hipEventRecord(side->fork, st))) return CKPT_E_HIP;
+            // every side stream waits for the D < 2 rows.  Nobody waits for the frontier kernel: the
+            // fill uses whatever frontier is in memory, and the group on its stream follows it anyway.
+            if (!hip_ok(hipEventRecord(side->fork, st))) return CKPT_E_HIP;
             for (int g = 1; g < groups; ++g) {
                 if (!hip_ok(hipStreamWaitEvent(gs[g], side->fork, 0))) return CKPT_E_HIP;
                 forked = g;
@@ -1615,7 +1636,7 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
             const int ks = want_ks ? want_ks : (waves <= 600 ? 4 : (waves <= 1700 ? 2 : 1));
             const int gx = (pitch / 64 + kCH / ks - 1) / (kCH / ks);
             for (int g = 0; g < groups; ++g) {
-                const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg, work};
+                const Ctx ctx{L, M, pitch, rows, first[g], spin_limit, ws, cost, arg, work};
                 const dim3 grid(gx, nblk - D, first[g + 1] - first[g]), block(64 * kCH);
                 const auto fn = ks == 4 ? (work ? gemm_kernel<3, 3, kCH / 4, 4, true> : gemm_kernel<3, 3, kCH / 4, 4, false>)
                               : ks == 2 ? (work ? gemm_kernel<3, 3, kCH / 2, 2, true> : gemm_kernel<3, 3, kCH / 2, 2, false>)
@@ -1632,7 +1653,7 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
             }
             if (fused_rows) {  // rows 6..0 of every tile of the diagonal in one launch per group
                 for (int g = 0; g < groups; ++g) {
-                    const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg, work};
+                    const Ctx ctx{L, M, pitch, rows, first[g], spin_limit, ws, cost, arg, work};
                     const auto fn = work ? tile_rows_kernel<2, true> : tile_rows_kernel<2, false>;
                     hipLaunchKernelGGL(fn, dim3(nbands, nblk - D, first[g + 1] - first[g]), dim3(kRowWG), 0, gs[g], ctx,
                                        D, ws.tick + D * kTickGroups + g);
@@ -1644,7 +1665,7 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
             // finished by the gemm
             for (int r = T - 2; r >= 0; --r) {
                 for (int g = 0; g < groups; ++g) {
-                    const Ctx ctx{L, M, pitch, rows, first[g], ws, cost, arg, work};
+                    const Ctx ctx{L, M, pitch, rows, first[g], spin_limit, ws, cost, arg, work};
                     hipLaunchKernelGGL(kRow2[r], dim3(gx_row, nblk - D, first[g + 1] - first[g]), dim3(kRowWG), 0,
                                        gs[g], ctx, D);
                     CKPT_AFTER_LAUNCH(CKPT_K_ROW);

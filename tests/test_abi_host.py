@@ -179,6 +179,10 @@ def test_options_are_validated_on_the_host(amd):
         o = _SolveOpts()
         o.groups, o.list_split = groups, split
         assert f(ctypes.byref(ch), 4, 8, 1, None, 256, 256, 256, ctypes.byref(o)) == -1, (groups, split)
+    for field, bad in (("row_launches", 2), ("row_launches", -1), ("frontier", 3), ("frontier", -1)):
+        o = _SolveOpts()
+        setattr(o, field, bad)
+        assert f(ctypes.byref(ch), 4, 8, 1, None, 256, 256, 256, ctypes.byref(o)) == -1, (field, bad)
     o = _SolveOpts()
     o.groups = 3
     o.side_streams[1] = 4096                                  # second side stream given, first missing

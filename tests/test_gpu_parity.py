@@ -166,12 +166,42 @@ def test_tables_do_not_depend_on_the_schedule(amd, oracle_mod, which):
                 dict(groups=4, list_split=2), dict(groups=2, list_split=4),
                 dict(groups=4, side_streams=[s.cuda_stream for s in own]),
                 dict(groups=3, list_split=1, side_streams=[s.cuda_stream for s in own[:2]]),
-                dict(row_launches=1), dict(groups=1, row_launches=1), dict(groups=4, row_launches=1, list_split=2)]
+                dict(row_launches=1), dict(groups=1, row_launches=1), dict(groups=4, row_launches=1, list_split=2),
+                dict(frontier=1), dict(frontier=2), dict(groups=1, frontier=1), dict(groups=4, frontier=2, stagger=1),
+                dict(groups=3, stagger=1, row_launches=1), dict(spin_limit=5000000)]
     for opts in variants:
         print(f"case {batch.name} {opts}", flush=True)
         other = amd.solve(batch, **opts)
         torch.cuda.synchronize()
         assert _same_tables(base, other, M), opts
+
+
+def test_a_wait_that_expires_is_reported_and_every_kernel_still_ends(amd):
+    """Failure path of the waits between work-groups, forced from the host: with spin_limit < 0
+    every read of a row that another band finishes in the same launch gives up at once.  The
+    kernels drain normally, ckpt_check_inputs reports CKPT_E_INTERNAL, and the next ordinary solve
+    into the same buffers is complete again."""
+    import torch
+    batch = random_chain_batch(40, 3000, 3, 61, size_hi=300, time_hi=2000, overheads=True)
+    L, M, B = batch.L, batch.M, batch.B
+    up = lambda a: None if a is None else torch.from_numpy(np.ascontiguousarray(a)).cuda()
+    uf, ub, wa, wabar = up(batch.uf), up(batch.ub), up(batch.wa), up(batch.wabar)
+    opt = dict(of=up(batch.of), ob=up(batch.ob))
+    cost = torch.empty(amd.ckpt_table_elems(L, M, B), dtype=torch.int32, device="cuda")
+    arg = torch.empty(amd.ckpt_table_elems(L, M, B), dtype=torch.uint8, device="cuda")
+    ws = torch.empty(amd.ckpt_workspace_bytes(L, M, B), dtype=torch.uint8, device="cuda")
+    amd.ckpt_solve_batched_opts(uf, ub, wa, wabar, L, M, B, cost, arg, ws, spin_limit=-1, **opt)
+    lib = amd.load_library()
+    flags = np.zeros(B, np.int32)
+    rc = lib.ckpt_check_inputs(ws.data_ptr(), L, M, B, None, flags.ctypes.data)
+    torch.cuda.synchronize()
+    assert rc == -9, rc
+    amd.ckpt_solve_batched(uf, ub, wa, wabar, L, M, B, cost, arg, ws, **opt)
+    assert amd.ckpt_check_inputs(ws, L, M, B).tolist() == [0] * B
+    ref = amd.solve(batch, row_launches=1)
+    pitch = amd.ckpt_row_pitch(M)
+    assert (cost.view(B, -1, pitch)[:, :, :M + 1] == ref.cost[:, :, :M + 1]).all()
+    assert (arg.view(B, -1, pitch)[:, :, :M + 1] == ref.arg[:, :, :M + 1]).all()
 
 
 def test_solve_with_other_streams_busy(amd, oracle_mod):
