@@ -1105,7 +1105,45 @@ __global__ void __launch_bounds__(kRowWG, 3) tile_rows_kernel(Ctx c, int D, int3
         }
     }
     x.par = &s_par;
+    // The band may lie past the end of the rows (pitch is a multiple of 64, not of kBand): those
+    // waves read and store nothing but still meet every barrier.
+    x.idle = x.m >= uint32_t(c.pitch);
     __syncthreads();
+    {   // A band below the feasibility frontier of every cell this kernel finishes in the tile: all of
+        // them are infeasible there.  Store that and leave (the whole work-group decides alike).
+        int tile_need = 1 << 30;
+        {   // every wave for itself: lane = cell, then a minimum over the wave
+            const int lane = threadIdx.x & 63, r = lane >> 3, cc = lane & 7;
+            if (r <= RF && cc >= (DC == 0 ? r : 0) && x.i0 + r < c.L && cc < x.cend) tile_need = s_par.need[r][cc];
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) tile_need = min(tile_need, __shfl_xor(tile_need, o));
+        }
+        if (int(min(uint32_t(x.band) * kBand + kBand - 1, uint32_t(c.pitch) - 1)) < tile_need) {
+            unsigned cells = 0;
+            if (!x.idle && !x.dead) {
+                for (int r = 0; r <= RF; ++r) {
+                    if (x.i0 + r >= c.L) continue;
+                    const uint32_t own = x.moff + s_par.rowoff[r];
+                    for (int cc = (DC == 0 ? r : 0); cc < x.cend; ++cc) {  // no dynamic index into x: it stays in registers
+                        const uint32_t col = uint32_t(cc) * uint32_t(c.pitch);
+                        __builtin_amdgcn_raw_buffer_store_b32(int(kInf), x.tab, int(own), int(col * 4u), 16);
+                        __builtin_amdgcn_raw_buffer_store_b8((unsigned char)(0), x.atab, int(own >> 2), int(col), 0);
+                        ++cells;
+                    }
+                }
+                count_work<CNT>(c.work, 2, 0, cells);
+                if (DC < 2) {  // readers in the bands above wait for this chunk's progress
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+                    __builtin_amdgcn_s_waitcnt(0);
+                    if ((threadIdx.x & 63) == 0)
+                        __hip_atomic_store(c.ws.prog + (size_t(x.b) * tiles_of(c.L) + tile_index(blocks_of(c.L), x.I, x.J)) *
+                                                           (c.pitch / 64) + (x.m >> 6),
+                                           RF + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            return;
+        }
+    }
     const int nblk = blocks_of(c.L);
     x.prog = c.ws.prog + (size_t(x.b) * tiles_of(c.L) + tile_index(nblk, x.I, x.J)) * (c.pitch / 64);
     x.chunk0 = x.band * (kBand / 64);
@@ -1115,9 +1153,6 @@ __global__ void __launch_bounds__(kRowWG, 3) tile_rows_kernel(Ctx c, int D, int3
         const int m0 = __builtin_amdgcn_readfirstlane(int(x.m));  // first column of the wave
         x.nwait = max(0, x.chunk0 - (max(0, m0 - reach) >> 6));
     }
-    // The band may lie past the end of the rows (pitch is a multiple of 64, not of kBand): those
-    // waves read and store nothing but still meet every barrier.
-    x.idle = x.m >= uint32_t(c.pitch);
     if (DC >= 1 && !x.dead && !x.idle) {
         // operands of the splits in the column block, finished by earlier launches
 #pragma unroll
