@@ -20,8 +20,9 @@ Prints ONE JSON line:
   other_workloads       the L = 96, B = 64 workload with the same figures
   cpu_baseline          the CPU oracle on a bounded sample of the same workload
 
-  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu] [--all] [--roofs]
-                  [--calib-copy MIB] [--groups G] [--row-launches 0|1] [--list-split 0|1|2|4]
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--config 4] [--no-cpu] [--all] [--roofs | --no-roofs]
+                  [--no-others] [--latency-solves N] [--calib-copy MIB]
+                  [--groups G] [--row-launches 0|1] [--list-split 0|1|2|4] [--stagger 1] [--frontier 0|1|2]
 """
 import argparse
 import ctypes
@@ -127,7 +128,7 @@ def run_config(amd, idx, steps, warmup, dev, profile=True, solves=10, sched=None
     assert not flags.any(), flags
     # every solve on its own: events on the launch stream (the solve forks from and joins into it)
     lat = []
-    for k in range(3 + max(1, solves)):
+    for k in range(3 + solves if solves > 0 else 0):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
@@ -152,7 +153,8 @@ def run_config(amd, idx, steps, warmup, dev, profile=True, solves=10, sched=None
                          bytes_stored_per_step=v[3]) for k, v in acc.items()}
     cells, evals = counts(L, M, B)
     return dict(batch=batch, ms=wall / steps * 1e3, cells=cells, evals=evals, kinds=kinds,
-                latency={"median": statistics.median(lat), "min": min(lat), "max": max(lat), "solves": len(lat)})
+                latency={"median": statistics.median(lat), "min": min(lat), "max": max(lat), "solves": len(lat)}
+                if lat else None)
 
 
 def roofline_of(r):
@@ -359,6 +361,8 @@ def main():
                                                        "single-chain case and the copy of the tables to the host")
     ap.add_argument("--roofs", action="store_true", help="full sweep of the roof microbenchmarks")
     ap.add_argument("--no-roofs", action="store_true", help="skip the roof microbenchmarks")
+    ap.add_argument("--no-others", action="store_true", help="skip the second workload (short counter runs)")
+    ap.add_argument("--latency-solves", type=int, default=10, help="solves timed on their own (0: none)")
     ap.add_argument("--groups", type=int, default=0, help="experiment: chain groups (0 automatic, 1 one stream)")
     ap.add_argument("--row-launches", type=int, default=0, help="experiment: 1 = one launch per tile row")
     ap.add_argument("--list-split", type=int, default=0, help="experiment: waves per work list, 0 automatic")
@@ -387,7 +391,7 @@ def main():
         sched = dict(groups=a.groups, row_launches=a.row_launches, list_split=a.list_split, stagger=a.stagger,
                      frontier=a.frontier)
 
-    r = run_config(amd, a.config, a.steps, a.warmup, dev, sched=sched)
+    r = run_config(amd, a.config, a.steps, a.warmup, dev, sched=sched, solves=a.latency_solves)
     batch = r["batch"]
     out = {
         "metric": "min-plus candidate evaluations per second (whole batch, tables resident in HBM)",
@@ -406,7 +410,7 @@ def main():
         "roofline": roofline_of(r),
     }
     others = {}
-    if a.config != 3:
+    if a.config != 3 and not a.no_others:
         o = run_config(amd, 3, 10, 3, dev, sched=sched)
         others[o["batch"].name] = dict(summary_of(o), roofline=roofline_of(o), kernels=o["kinds"])
     if a.all:

@@ -837,13 +837,14 @@ __device__ __forceinline__ void wait_rows_below(TileCtx<DC>& x, int rows) {
 // D >= 2: the cells of the tile hold the gemm's partial minima, marked by bit 31, until their
 // row is finished, so the read needs no flag: a lane that finds the mark reads again (bounded).
 // D < 2: the caller has waited for the progress flags of the chunks that are read.
-template <int DC, bool FULL>
+template <int DC, bool FULL, bool CNT>
 __device__ __forceinline__ void read_row_below(TileCtx<DC>& x, const uint32_t (*below)[kBand], uint32_t rowoff,
                                                uint32_t sh, int first_cc, uint32_t (&out)[kT]) {
     const int cend = FULL ? kT : x.cend;
     const int t = int(threadIdx.x) - int(sh);  // column inside the band
     const bool in_band = t >= 0;
     const uint32_t voff = (!in_band && x.m >= sh) ? x.moff + rowoff - 4 * sh : kNoRead;
+    if (CNT && __any(voff != kNoRead)) count_work<CNT>(x.c.work, 2, unsigned(max(0, cend - first_cc)), 0);
     uint32_t mem[kT];
     auto fetch = [&]() {
         uint32_t marks = 0;
@@ -910,7 +911,7 @@ __device__ __forceinline__ void tile_row(TileCtx<DC>& x, uint32_t (*s_row)[kT][k
         if ((U < T || DC == 1) && x.i0 + U < L) {
             const uint32_t sh = uint32_t(par.wsh[U]);
             if (below_here) {
-                read_row_below<DC, FULL>(x, below, par.rowoff[U], sh, DC == 0 ? U : 0, x.ri[U]);
+                read_row_below<DC, FULL, CNT>(x, below, par.rowoff[U], sh, DC == 0 ? U : 0, x.ri[U]);
             } else {  // finished by an earlier launch
                 const uint32_t voff = m >= sh ? moff + par.rowoff[U] - 4 * sh : kNoRead;
 #pragma unroll
@@ -925,7 +926,11 @@ __device__ __forceinline__ void tile_row(TileCtx<DC>& x, uint32_t (*s_row)[kT][k
         const int m_hi = __builtin_amdgcn_readfirstlane(int(m)) | 63;
         const bool live = m_hi >= row_need;  // else the whole chunk lies below the feasibility frontier of the row
         const unsigned cols = unsigned(max(0, cend - CF));  // cells of the row that exist
-        count_work<CNT>(x.c.work, 2, cols + (live ? unsigned(NQ) + (DC == 2 ? 10u : 0u) + cols : 0u), cols);
+        // loads from earlier launches: the row below (first row of the kernel only), left operands, the
+        // gemm's partial minima (cost + number), C_all operands (first row only); reads of rows of this
+        // launch are counted where they are issued, and only for waves that reach below their band
+        count_work<CNT>(x.c.work, 2, (below_here ? 0u : cols) + (live ? unsigned(NQ) + (DC == 2 ? 10u : 0u) +
+                                                                          (below_here ? 0u : cols) : 0u), cols);
         const uint32_t Pi = par.Pi[R];
         const uint32_t fbi = par.fb[R];
         const uint32_t wabi = par.wabs[R];
@@ -948,7 +953,7 @@ __device__ __forceinline__ void tile_row(TileCtx<DC>& x, uint32_t (*s_row)[kT][k
             }
             // C_all: cell (i + 1, j) at m - omega_abar^{i+1}, for j > i
             if (below_here) {
-                read_row_below<DC, FULL>(x, below, par.rowoff[U], wabi, DC == 0 ? CF + 1 : CF, al);
+                read_row_below<DC, FULL, CNT>(x, below, par.rowoff[U], wabi, DC == 0 ? CF + 1 : CF, al);
             } else if (i + 1 < L) {  // row 0 of the tile below, or row 7 finished by the gemm: earlier launches
                 const uint32_t voff = m >= wabi ? moff + par.rowoff[U] - 4 * wabi : kNoRead;
 #pragma unroll
