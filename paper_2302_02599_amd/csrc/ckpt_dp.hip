@@ -1670,10 +1670,13 @@ int solve_impl(const ckpt_chains_t* chains, int L, int M, int B, void* stream, i
             }
         }
         for (int D = 2; D < nblk; ++D) {
-            // The last diagonals have few tiles: when all groups together bring fewer waves than
-            // the chip holds, 2 or 4 waves share each chunk and split its work list.
+            // Later diagonals have fewer tiles and longer work lists.  The chip holds 2048 of these
+            // waves; once a launch brings fewer than about three and a half times that, whole-list
+            // waves leave the machine half empty while the last ones finish, so 2 waves share each
+            // chunk and split its list (measured: a gain from there on, a loss with more tiles,
+            // where the lists are short); with fewer waves than a quarter of the chip, 4 do.
             const long long waves = (long long)(nblk - D) * (pitch / 64) * B;
-            const int ks = want_ks ? want_ks : (waves <= 600 ? 4 : (waves <= 1700 ? 2 : 1));
+            const int ks = want_ks ? want_ks : (waves <= 600 ? 4 : (waves <= 7000 ? 2 : 1));
             const int gx = (pitch / 64 + kCH / ks - 1) / (kCH / ks);
             for (int g = 0; g < groups; ++g) {
                 const Ctx ctx{L, M, pitch, rows, first[g], spin_limit, ws, cost, arg, work};
