@@ -398,16 +398,17 @@ __device__ __forceinline__ void finish_row(const Ctx& c, size_t chain, const int
 // Middle splits of every tile of block diagonal D >= 2.
 // One wave owns the 8x8 tile of cells for 64 consecutive m; lane = m.  Each loaded operand
 // row is used by 8 cells (1 byte of table traffic per candidate instead of 8).  The CH waves of
-// a work-group take adjacent chunks of m of the same tile: they share one work list, and the
-// cache lines that a shifted operand read straddles are fetched once for two waves.
+// a work-group take adjacent chunks of m of the same tile: the cache lines that a shifted
+// operand read straddles are fetched once for two waves.
 // Candidates are compared as float64 keys  cost + (q+1)/256 : one add and one min per
 // candidate give the minimum cost and, among equal costs, the smallest candidate number
 // (all values are integers below 2^34 scaled by 2^-8, exact in float64).
 // Splits whose operands are infeasible for the whole chunk (frontier test) are dropped
 // from the work list before the pipeline starts.
 // Output, rows 0..6 of the tile: cost[] <- partial minimum clamped to 2^31 - 1, with bit 31 set as
-// the mark "not finished", arg[] <- its number; the row kernels finish them.  Row 7 has no split in its own row block, so
-// its partial minimum stays in registers and the wave finishes the row itself.
+// the mark "not finished", arg[] <- its number; the row kernels finish them.  Row 7 has no split
+// in its own row block, so its partial minimum stays in registers and the wave finishes the row
+// itself.
 // KS > 1 (launches with too few tiles to fill the chip): KS waves share one chunk, each takes
 // every KS-th entry of the work list, and their key tiles are merged through LDS at the end.
 template <int NB, int UNR, int CH, int KS, bool CNT>
@@ -425,7 +426,6 @@ __global__ void __launch_bounds__(64 * CH * KS, 2) gemm_kernel(Ctx c, int D) {
     const int cw = wave / KS, slice = wave % KS;  // chunk within the work-group, slice of the list
     const int chunk = bx * CH + cw;  // this wave's 64 columns of m
     const uint32_t m = chunk * 64 + lane;
-    const int m_hi = min((bx * CH + CH) * 64, pitch) - 1;  // largest m of the work-group
     const uint32_t moff = m * 4;
     const size_t chain = size_t(b) * c.rows * pitch;
     const rsrc_t tab = table_rsrc(c.cost + chain, uint32_t(c.rows) * uint32_t(pitch) * 4u);
@@ -437,22 +437,25 @@ __global__ void __launch_bounds__(64 * CH * KS, 2) gemm_kernel(Ctx c, int D) {
 #pragma unroll
     for (int cc = 0; cc < 8; ++cc) jcol[cc] = min(j0 + cc, L - 1);
 
-    // Work list of the work-group: the splits q for which some cell of the tile can have both
-    // operands feasible somewhere in its CH chunks.  Per-split constants (shift, key offset)
-    // travel with the list through LDS, so the pipeline never waits on scalar memory.
-    __shared__ double s_kq[CKPT_MAX_L + 2];
-    __shared__ int32_t s_sh[CKPT_MAX_L + 2];
-    __shared__ int32_t s_q[CKPT_MAX_L + 2];
-    __shared__ int32_t s_n;
-    if (wave == 0) {
+    // Work list of the chunk: the splits q for which some cell of the tile can have both operands
+    // feasible somewhere in these 64 columns.  Per-split constants (shift, key offset) travel
+    // with the list through LDS, so the pipeline never waits on scalar memory.  Every chunk of
+    // the work-group has a list of its own, built by its (first) wave: the lower chunks of a
+    // work-group drop splits that only its highest chunk can use.
+    __shared__ double s_kq[CKPT_MAX_L + 2][CH];
+    __shared__ int2 s_qs[CKPT_MAX_L + 2][CH];  // .x = q, .y = its shift: one LDS read per entry
+    __shared__ int32_t s_n[CH];
+    const bool active = chunk * 64 < pitch;
+    if (slice == 0) {
+        const int m_hi = min(chunk * 64 + 63, pitch - 1);  // largest m of the chunk
         int n = 0;
         int out_need = need[(i0 + (lane >> 3)) * L + min(j0 + (lane & 7), L - 1)];
 #pragma unroll
         for (int o = 32; o > 0; o >>= 1) out_need = min(out_need, __shfl_xor(out_need, o));
-        if (m_hi >= out_need) {
+        if (active && m_hi >= out_need) {
             for (int base = qlo; base <= qhi; base += 64) {
                 const int q = base + lane;
-                bool active = false;
+                bool on = false;
                 int sh = 0;
                 if (q <= qhi) {
                     sh = c.ws.wsh[size_t(b) * L + q];
@@ -461,25 +464,29 @@ __global__ void __launch_bounds__(64 * CH * KS, 2) gemm_kernel(Ctx c, int D) {
                     for (int r = 0; r < 8; ++r) tl = min(tl, need[(i0 + r) * L + q - 1]);
 #pragma unroll
                     for (int cc = 0; cc < 8; ++cc) tr = min(tr, need[q * L + jcol[cc]]);
-                    active = m_hi >= max(tl, tr + sh);
+                    on = m_hi >= max(tl, tr + sh);
                 }
-                const unsigned long long mask = __ballot(active);
-                if (active) {
+                const unsigned long long mask = __ballot(on);
+                if (on) {
                     const int pos = n + __popcll(mask & ((1ull << lane) - 1ull));
-                    s_q[pos] = q;
-                    s_sh[pos] = sh;
-                    s_kq[pos] = c.ws.kq[size_t(b) * L + q];
+                    s_qs[pos][cw] = make_int2(q, sh);
+                    s_kq[pos][cw] = c.ws.kq[size_t(b) * L + q];
                 }
                 n += __popcll(mask);
             }
         }
-        if (lane == 0) s_n = n;
+        if (lane == 0) s_n[cw] = n;
     }
-    __syncthreads();
-    const bool active = chunk * 64 < pitch;
-    if (KS == 1 && !active) return;  // KS > 1: every wave stays for the barriers of the merge
+    if constexpr (KS > 1) {
+        __syncthreads();  // the other slices of the chunk read the list
+    } else {
+        if (!active) return;  // KS > 1: every wave stays for the barriers of the merge
+        __builtin_amdgcn_wave_barrier();  // the wave reads what its own lanes wrote: LDS keeps a wave's order
+        __builtin_amdgcn_sched_barrier(0);
+    }
     // this wave's entries: slice, slice + KS, ...
-    const int n = active && s_n > slice ? (s_n - slice + KS - 1) / KS : 0;
+    const int n_all = __builtin_amdgcn_readfirstlane(s_n[cw]);
+    const int n = active && n_all > slice ? (n_all - slice + KS - 1) / KS : 0;
     auto entry = [&](int t) { return slice + KS * t; };
 
     double key[8][8];
@@ -492,8 +499,9 @@ __global__ void __launch_bounds__(64 * CH * KS, 2) gemm_kernel(Ctx c, int D) {
         uint32_t buf[NB][16];
         auto load = [&](uint32_t(&v)[16], int t) {
             const int k = entry(t);
-            const int q = __builtin_amdgcn_readfirstlane(s_q[k]);
-            const int sh = __builtin_amdgcn_readfirstlane(s_sh[k]);
+            const int2 qs = s_qs[k][cw];
+            const int q = __builtin_amdgcn_readfirstlane(qs.x);
+            const int sh = __builtin_amdgcn_readfirstlane(qs.y);
             const int rq = q * L - (q * (q - 1)) / 2 - q;  // + j = row of (q, j)
 #pragma unroll
             for (int r = 0; r < 8; ++r) v[r] = ld32(tab, uint32_t(lrow0[r] + q) * uint32_t(pitch), moff);
@@ -502,7 +510,7 @@ __global__ void __launch_bounds__(64 * CH * KS, 2) gemm_kernel(Ctx c, int D) {
                 v[8 + cc] = ld32(tab, uint32_t(rq + jcol[cc]) * uint32_t(pitch) - uint32_t(sh), moff);
         };
         auto compute = [&](const uint32_t(&v)[16], int t) {
-            const double cq = s_kq[entry(t)];
+            const double cq = s_kq[entry(t)][cw];
             double lk[8], rk[8];
 #pragma unroll
             for (int r = 0; r < 8; ++r) lk[r] = double(v[r]);
