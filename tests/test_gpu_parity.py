@@ -69,6 +69,7 @@ def test_random_shapes(amd, oracle_mod, seed):
     (40, 36000, 3, 33, 1200),     # large enough for the multi-stream schedule: three groups of one chain
     (32, 30000, 5, 35, 1000),     # four groups of 1, 1, 1 and 2 chains
     (10, 100, 700, 34, 9),        # more chains than threads of any block
+    (254, 4096, 2, 36, 120),      # the longest chain the library takes, at the width of the benchmark
 ])
 def test_wide_rows_and_many_chains(amd, oracle_mod, L, M, B, seed, size_hi):
     batch = random_chain_batch(L, M, B, seed, size_hi=size_hi, time_hi=5000, overheads=True, own_wdelta=True)
