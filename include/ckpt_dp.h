@@ -36,7 +36,7 @@
  *
  * Ownership and threading: every buffer belongs to the caller and must stay valid
  * until the work enqueued on the stream has finished.  The library's only state is the
- * last HIP error code and, per device, three helper streams with four events (see
+ * last HIP error code and, per device, three helper streams with five events (see
  * ckpt_init) on which ckpt_solve_batched runs up to three quarters of a large batch,
  * forked from and joined back into the caller's stream.  A solve with
  * ckpt_solve_opts_t.groups = 1 touches none of it.  Calls from several threads and on

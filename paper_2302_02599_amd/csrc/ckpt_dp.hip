@@ -1474,7 +1474,7 @@ struct Profile {
     } while (0)
 
 // Per-device state of the library, kept for the life of the process:
-//   helpers  three streams (default priority, non-blocking) and four events for the batch split;
+//   helpers  three streams (default priority, non-blocking) and five events for the batch split;
 //            with the caller's stream they make four, the number of hardware queues a process
 //            gets by default (more streams than that share queues and serialise: six or eight
 //            groups measured slower than one).  Created by ckpt_init or by the first solve
